@@ -1,0 +1,196 @@
+/*
+ * card.h - C ABI of libcard: the target model's multi-token verification step of CARD
+ * (query-and-correct speculative decoding) on one MI355X (gfx950), plus the shared
+ * candidate cache the target queries and corrects.
+ *
+ * What one verification step is (CARD Design, overview figure and its caption; Cache
+ * Correction, last paragraph; Comparing with Tree-Verified Methods): the target model
+ * forwards the chain of r candidate tokens picked from the shared cache in a single
+ * plain-causal pass against its existing KV cache, compares its own arg-max prediction
+ * with each candidate, keeps the longest matching prefix and emits its own next token,
+ * which corrects the draft side.  At temperature 0 this reproduces plain greedy decoding
+ * of the target exactly (lossless).
+ *
+ * Conventions for every function
+ *   - returns CARD_OK (0) or a negative card_status; never throws, aborts or prints;
+ *   - "dev" pointers are device memory of the current HIP device, "host" pointers are
+ *     ordinary host memory; every device buffer is owned by the caller and must stay
+ *     alive until the stream has finished the call;
+ *   - device work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and is asynchronous; no function synchronises unless it says so;
+ *   - argument errors are detected on the host before anything is enqueued.
+ *   - the library allocates no device memory.
+ */
+#ifndef CARD_H
+#define CARD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum card_status {
+    CARD_OK = 0,
+    CARD_EINVAL = -1,    /* null pointer, non-positive size, unsupported shape            */
+    CARD_ERANGE = -2,    /* r outside [1, max_r], level / index outside the cache         */
+    CARD_ECAPACITY = -3, /* ctx_len + r exceeds max_ctx or the block table                 */
+    CARD_EDEVICE = -4,   /* a HIP call failed (launch error, wrong device architecture)    */
+    CARD_ESTALE = -5     /* cache write refers to an epoch that a correction has ended     */
+} card_status;
+
+const char* card_strerror(int status);
+
+/* ------------------------------------------------------------------------------------------
+ * Model description.  Decoder-only, pre-norm: RMSNorm, rotary embedding with half-split
+ * pairing, grouped-query attention, SwiGLU feed-forward, untied vocabulary head, no biases
+ * (the LLaMA / Qwen families named in Experimental Setup, "Models and Datasets").
+ * Constraints: head_dim in {64, 128}; d_model, n_q_heads*head_dim and d_ffn multiples of 16;
+ * n_q_heads a multiple of n_kv_heads; kv_block == 16; 1 <= max_r <= 32.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct card_model_cfg {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rope_theta, rms_eps;
+    int32_t kv_block; /* tokens per KV page: 16                                             */
+    int32_t max_ctx;  /* capacity of the block table in tokens (multiple of kv_block)       */
+    int32_t max_r;    /* largest r a call may pass (<= 32)                                  */
+} card_model_cfg;
+
+/* Tensors of the canonical (caller-side) weight set. Matrices are bf16, row-major
+ * [out_features][in_features]; gains are fp32 vectors of d_model entries. */
+typedef enum card_tensor {
+    CARD_T_EMBED = 0,  /* [vocab][d_model]                      layer ignored */
+    CARD_T_WQ = 1,     /* [n_q_heads*head_dim][d_model]                       */
+    CARD_T_WK = 2,     /* [n_kv_heads*head_dim][d_model]                      */
+    CARD_T_WV = 3,     /* [n_kv_heads*head_dim][d_model]                      */
+    CARD_T_WO = 4,     /* [d_model][n_q_heads*head_dim]                       */
+    CARD_T_WG = 5,     /* [d_ffn][d_model]   gate                             */
+    CARD_T_WU = 6,     /* [d_ffn][d_model]   up                               */
+    CARD_T_WD = 7,     /* [d_model][d_ffn]   down                             */
+    CARD_T_LM_HEAD = 8,/* [vocab][d_model]                      layer ignored */
+    CARD_T_G_ATTN = 9, /* fp32 [d_model]  gain of the norm before attention   */
+    CARD_T_G_FFN = 10, /* fp32 [d_model]  gain of the norm before the FFN     */
+    CARD_T_G_FINAL = 11/* fp32 [d_model]                        layer ignored */
+} card_tensor;
+
+/* Sizes of the caller-allocated device buffers (bytes; 0 if cfg is invalid). */
+size_t card_packed_weight_bytes(const card_model_cfg* cfg);
+size_t card_workspace_bytes(const card_model_cfg* cfg);
+/* bytes of ONE of the two page pools (K or V) holding n_pages pages for all layers */
+size_t card_kv_pool_bytes(const card_model_cfg* cfg, int32_t n_pages);
+
+/* Re-lays one canonical tensor (src_dev, device memory, layout above) into its place inside
+ * the packed weight blob (packed_dev, card_packed_weight_bytes(cfg) bytes).  The packed
+ * layout stores every matrix as 16x32 tiles in the register order of the gfx950 bf16 matrix
+ * instruction so the verify kernels stream it with fully contiguous 1 KiB wavefront loads;
+ * values are moved, never changed.  Call once per tensor (per layer for layer tensors). */
+int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t layer,
+                             const void* src_dev, void* packed_dev, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Paged KV cache of the target model (bf16).  k_pages / v_pages each hold
+ * card_kv_pool_bytes(cfg, n_pages) bytes; page p of layer l starts at
+ * ((l * n_pages + p) * n_kv_heads) * 16 * head_dim elements.  Token position t lives in page
+ * block_table[t / 16], slot t % 16.  Inside a page K is stored after rotation, in
+ * [head_dim/8][16 tokens][8] order, V in [head_dim][16 tokens] order (use card_kv_gather to
+ * read them back in plain order).
+ * ---------------------------------------------------------------------------------------- */
+typedef struct card_kv {
+    void* k_pages;              /* dev */
+    void* v_pages;              /* dev */
+    const int32_t* block_table; /* dev, max_ctx/16 entries, each in [0, n_pages)            */
+    int32_t n_pages;
+    int32_t pending_token;      /* the target's own prediction for position ctx_len (the last
+                                   call's correction_token, or the arg-max after prefill);
+                                   -1 = none: the first candidate is taken as given          */
+} card_kv;
+
+typedef struct card_verify_result {
+    int32_t accepted_len;     /* 0..r: length of the longest prefix of the candidates that
+                                 equals the target's own greedy tokens                       */
+    int32_t correction_token; /* the target's token for position ctx_len + accepted_len      */
+    int32_t kv_first_slot;    /* == ctx_len                                                  */
+    int32_t kv_count;         /* == accepted_len: positions [first, first+count) of the KV
+                                 cache now hold verified tokens; later ones are stale and
+                                 are overwritten by the next call                            */
+} card_verify_result;
+
+/* One verification step (overview figure, steps 1-3: forward the queried path, accept the
+ * matching prefix, emit the next token).  Forwards the r candidates at positions
+ * ctx_len .. ctx_len+r-1 against kv[0, ctx_len), causal among themselves; writes K and V of
+ * all r rows into the cache; candidate i is accepted iff every earlier one was and it equals
+ * pred[i], where pred[0] = kv->pending_token and pred[i] = arg-max (lowest index on ties) of
+ * row i-1's vocabulary logits.  Logits are never written to memory.
+ *   packed_weights_dev : blob filled by card_weights_pack_tensor
+ *   kv                 : host struct (read during the call only)
+ *   cand_tokens_dev    : dev, r int32 token ids in [0, vocab)
+ *   workspace_dev      : dev, card_workspace_bytes(cfg) bytes, contents irrelevant on entry
+ *                        except that the caller zeroes it once after allocation
+ *   out_dev            : dev (or device-visible pinned host) card_verify_result
+ *   row_argmax_dev     : dev, optional (may be NULL): r int32, arg-max of each row
+ * Errors: CARD_EINVAL, CARD_ERANGE (r), CARD_ECAPACITY (ctx_len + r > max_ctx); nothing is
+ * enqueued on error.  Token ids are not range-checked on the host (they are on the device:
+ * an id outside [0, vocab) is clamped). */
+int card_verify(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
+                int32_t ctx_len, const int32_t* cand_tokens_dev, int32_t r, void* workspace_dev,
+                void* stream, card_verify_result* out_dev, int32_t* row_argmax_dev);
+
+/* Test entry point, not on the timed path: the same forward, additionally storing the fp32
+ * logits [r][vocab] (dev) so that tests can bound the error of the final-layer logits. */
+int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weights_dev,
+                             const card_kv* kv, int32_t ctx_len, const int32_t* cand_tokens_dev,
+                             int32_t r, void* workspace_dev, void* stream,
+                             card_verify_result* out_dev, int32_t* row_argmax_dev,
+                             float* logits_dev);
+
+/* Test helper: copies K (rotated) and V of positions [first_slot, first_slot+count) of one
+ * layer out of the paged cache into plain fp32 arrays [count][n_kv_heads][head_dim] (dev). */
+int card_kv_gather(const card_model_cfg* cfg, const card_kv* kv, int32_t layer,
+                   int32_t first_slot, int32_t count, float* k_out_dev, float* v_out_dev,
+                   void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Shared candidate cache (Cache Construction, eqs. (1)-(9); Cache Correction).  A host object:
+ * a tree whose level l is the primary cache C^(l) - at most K nodes (token, path score w of
+ * eq. (3), index of the parent in level l-1, i.e. the tuples of the secondary cache, eq. (5),
+ * that survived the top-K selection of eqs. (6)-(7)).  Level 0 holds the candidates for the
+ * next position the target has not verified.  One writer (draft side) and one reader (target
+ * side) may call concurrently: every function takes the object's lock.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct card_cache card_cache;
+
+int card_cache_create(int32_t K, int32_t max_depth, card_cache** out);
+void card_cache_destroy(card_cache* c);
+
+/* Draft side: store level `level` (<= current depth; an existing level is replaced and deeper
+ * ones dropped).  tokens / parent_idx / path_score: host arrays of n <= K entries; parents
+ * index level-1 and are -1 at level 0.  `epoch` must equal card_cache_epoch() as read when
+ * the writer last synchronised with the corrections, else CARD_ESTALE and nothing changes. */
+int card_cache_write(card_cache* c, int64_t epoch, int32_t level, int32_t n, const int32_t* tokens,
+                     const int32_t* parent_idx, const float* path_score);
+
+/* Target side, before a step: look the just-verified token up among the level-0 nodes (the
+ * best-scored one on duplicates).  On a hit writes the best path below it - starting with the
+ * verified token itself, following parent links down to the highest-scored descendant on the
+ * deepest reachable level, at most max_len tokens - and returns 1; returns 0 on a miss. */
+int card_cache_query(const card_cache* c, int32_t verified_token, int32_t max_len,
+                     int32_t* out_tokens, int32_t* out_len, float* out_score);
+
+/* Target side, after a step: walk the n verified tokens down from level 0, make the children of
+ * the last matched node the new level 0 and drop everything outside its subtree (a rejected
+ * path's siblings stay available).  A token without a node empties the cache.  Increments the
+ * epoch.  Returns 1 if the chain was found, 0 if the cache was emptied. */
+int card_cache_correct(card_cache* c, const int32_t* verified_tokens, int32_t n);
+
+int64_t card_cache_epoch(const card_cache* c);
+int32_t card_cache_depth(const card_cache* c);
+/* copies level `level` out (host arrays of at least K entries; any may be NULL); returns the
+ * node count or a negative status */
+int card_cache_read_level(const card_cache* c, int32_t level, int32_t* tokens, int32_t* parent_idx,
+                          float* path_score);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CARD_H */

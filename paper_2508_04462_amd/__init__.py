@@ -1,0 +1,39 @@
+"""MI355X-native verification step of CARD (query-and-correct speculative decoding).
+
+The work is done by libcard.so (hand-written HIP for gfx950 behind the C ABI of
+include/card.h).  This package only marshals arguments; PyTorch supplies device
+memory and streams.  Importing the package loads the library and fails loudly if
+it has not been built (python -m paper_2508_04462_amd.build).
+"""
+from .binding import (  # noqa: F401
+    CARD_OK,
+    CARD_EINVAL,
+    CARD_ERANGE,
+    CARD_ECAPACITY,
+    CARD_EDEVICE,
+    CARD_ESTALE,
+    TENSOR_IDS,
+    CardError,
+    CardModelCfg,
+    CardKV,
+    CardVerifyResult,
+    lib,
+    lib_path,
+    card_strerror,
+    card_packed_weight_bytes,
+    card_workspace_bytes,
+    card_kv_pool_bytes,
+    card_weights_pack_tensor,
+    card_verify,
+    card_verify_debug_logits,
+    card_kv_gather,
+    card_cache_create,
+    card_cache_destroy,
+    card_cache_write,
+    card_cache_query,
+    card_cache_correct,
+    card_cache_epoch,
+    card_cache_depth,
+    card_cache_read_level,
+)
+from .runtime import Target, CandidateCache, make_cfg  # noqa: F401

@@ -1,0 +1,193 @@
+"""ctypes binding of include/card.h: same names, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(_PKG, "libcard.so")
+
+CARD_OK, CARD_EINVAL, CARD_ERANGE, CARD_ECAPACITY, CARD_EDEVICE, CARD_ESTALE = 0, -1, -2, -3, -4, -5
+
+TENSOR_IDS = {
+    "embed": 0, "wq": 1, "wk": 2, "wv": 3, "wo": 4, "wg": 5, "wu": 6, "wd": 7,
+    "lm_head": 8, "g_attn": 9, "g_ffn": 10, "g_final": 11,
+}
+
+
+class CardError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {card_strerror(status)} ({status})")
+
+
+class CardModelCfg(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+        ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
+        ("vocab", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float),
+        ("kv_block", C.c_int32), ("max_ctx", C.c_int32), ("max_r", C.c_int32),
+    ]
+
+
+class CardKV(C.Structure):
+    _fields_ = [
+        ("k_pages", C.c_void_p), ("v_pages", C.c_void_p), ("block_table", C.c_void_p),
+        ("n_pages", C.c_int32), ("pending_token", C.c_int32),
+    ]
+
+
+class CardVerifyResult(C.Structure):
+    _fields_ = [
+        ("accepted_len", C.c_int32), ("correction_token", C.c_int32),
+        ("kv_first_slot", C.c_int32), ("kv_count", C.c_int32),
+    ]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(lib_path):
+        raise ImportError(
+            f"{lib_path} is missing: build it with `python -m paper_2508_04462_amd.build` "
+            "(there is no fallback path)")
+    return C.CDLL(lib_path)
+
+
+lib = _load()
+
+_P = C.c_void_p
+_cfgp = C.POINTER(CardModelCfg)
+_kvp = C.POINTER(CardKV)
+_i32p = C.POINTER(C.c_int32)
+_f32p = C.POINTER(C.c_float)
+
+lib.card_strerror.restype = C.c_char_p
+lib.card_strerror.argtypes = [C.c_int]
+for _n in ("card_packed_weight_bytes", "card_workspace_bytes"):
+    getattr(lib, _n).restype = C.c_size_t
+    getattr(lib, _n).argtypes = [_cfgp]
+lib.card_kv_pool_bytes.restype = C.c_size_t
+lib.card_kv_pool_bytes.argtypes = [_cfgp, C.c_int32]
+lib.card_weights_pack_tensor.restype = C.c_int
+lib.card_weights_pack_tensor.argtypes = [_cfgp, C.c_int32, C.c_int32, _P, _P, _P]
+lib.card_verify.restype = C.c_int
+lib.card_verify.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P]
+lib.card_verify_debug_logits.restype = C.c_int
+lib.card_verify_debug_logits.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P, _P]
+lib.card_kv_gather.restype = C.c_int
+lib.card_kv_gather.argtypes = [_cfgp, _kvp, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P]
+lib.card_cache_create.restype = C.c_int
+lib.card_cache_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(_P)]
+lib.card_cache_destroy.restype = None
+lib.card_cache_destroy.argtypes = [_P]
+lib.card_cache_write.restype = C.c_int
+lib.card_cache_write.argtypes = [_P, C.c_int64, C.c_int32, C.c_int32, _i32p, _i32p, _f32p]
+lib.card_cache_query.restype = C.c_int
+lib.card_cache_query.argtypes = [_P, C.c_int32, C.c_int32, _i32p, _i32p, _f32p]
+lib.card_cache_correct.restype = C.c_int
+lib.card_cache_correct.argtypes = [_P, _i32p, C.c_int32]
+lib.card_cache_epoch.restype = C.c_int64
+lib.card_cache_epoch.argtypes = [_P]
+lib.card_cache_depth.restype = C.c_int32
+lib.card_cache_depth.argtypes = [_P]
+lib.card_cache_read_level.restype = C.c_int
+lib.card_cache_read_level.argtypes = [_P, C.c_int32, _i32p, _i32p, _f32p]
+
+
+def _ptr(x) -> Optional[int]:
+    """torch tensor -> its data pointer; int / None pass through."""
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+def card_strerror(status: int) -> str:
+    return lib.card_strerror(int(status)).decode()
+
+
+def card_packed_weight_bytes(cfg: CardModelCfg) -> int:
+    return lib.card_packed_weight_bytes(C.byref(cfg))
+
+
+def card_workspace_bytes(cfg: CardModelCfg) -> int:
+    return lib.card_workspace_bytes(C.byref(cfg))
+
+
+def card_kv_pool_bytes(cfg: CardModelCfg, n_pages: int) -> int:
+    return lib.card_kv_pool_bytes(C.byref(cfg), n_pages)
+
+
+def card_weights_pack_tensor(cfg, tensor: int, layer: int, src_dev, packed_dev, stream=None) -> int:
+    return lib.card_weights_pack_tensor(C.byref(cfg), tensor, layer, _ptr(src_dev), _ptr(packed_dev), _ptr(stream))
+
+
+def card_verify(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: int, workspace_dev, stream,
+                out_dev, row_argmax_dev=None) -> int:
+    return lib.card_verify(C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, _ptr(cand_dev), r,
+                           _ptr(workspace_dev), _ptr(stream), _ptr(out_dev), _ptr(row_argmax_dev))
+
+
+def card_verify_debug_logits(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: int, workspace_dev,
+                             stream, out_dev, row_argmax_dev, logits_dev) -> int:
+    return lib.card_verify_debug_logits(C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, _ptr(cand_dev), r,
+                                        _ptr(workspace_dev), _ptr(stream), _ptr(out_dev), _ptr(row_argmax_dev),
+                                        _ptr(logits_dev))
+
+
+def card_kv_gather(cfg, kv: CardKV, layer: int, first_slot: int, count: int, k_out_dev, v_out_dev,
+                   stream=None) -> int:
+    return lib.card_kv_gather(C.byref(cfg), C.byref(kv), layer, first_slot, count, _ptr(k_out_dev),
+                              _ptr(v_out_dev), _ptr(stream))
+
+
+def _i32(seq):
+    return (C.c_int32 * len(seq))(*[int(v) for v in seq])
+
+
+def card_cache_create(K: int, max_depth: int):
+    h = _P()
+    st = lib.card_cache_create(K, max_depth, C.byref(h))
+    return st, h
+
+
+def card_cache_destroy(handle) -> None:
+    lib.card_cache_destroy(handle)
+
+
+def card_cache_write(handle, epoch: int, level: int, tokens, parent_idx, path_score) -> int:
+    n = len(tokens)
+    sc = (C.c_float * n)(*[float(v) for v in path_score])
+    return lib.card_cache_write(handle, epoch, level, n, _i32(tokens), _i32(parent_idx), sc)
+
+
+def card_cache_query(handle, verified_token: int, max_len: int):
+    """Returns (status_or_hit, tokens, score)."""
+    buf = (C.c_int32 * max(1, max_len))()
+    n = C.c_int32(0)
+    sc = C.c_float(0.0)
+    st = lib.card_cache_query(handle, verified_token, max_len, buf, C.byref(n), C.byref(sc))
+    return st, list(buf[: n.value]), sc.value
+
+
+def card_cache_correct(handle, verified_tokens) -> int:
+    return lib.card_cache_correct(handle, _i32(verified_tokens), len(verified_tokens))
+
+
+def card_cache_epoch(handle) -> int:
+    return lib.card_cache_epoch(handle)
+
+
+def card_cache_depth(handle) -> int:
+    return lib.card_cache_depth(handle)
+
+
+def card_cache_read_level(handle, level: int, K: int):
+    t = (C.c_int32 * K)()
+    p = (C.c_int32 * K)()
+    s = (C.c_float * K)()
+    n = lib.card_cache_read_level(handle, level, t, p, s)
+    if n < 0:
+        return n, [], [], []
+    return n, list(t[:n]), list(p[:n]), list(s[:n])

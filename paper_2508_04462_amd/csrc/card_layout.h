@@ -1,0 +1,169 @@
+// Host-side description of where everything lives: the packed weight blob, the workspace,
+// and how each weight-streaming GEMM is cut into tasks.  Plain structs, passed to kernels by value.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include "card.h"
+
+namespace card {
+
+constexpr int kTileN = 16;     // rows of one matrix-instruction tile (output features)
+constexpr int kTileK = 32;     // contraction depth of one bf16 16x16x32 matrix instruction
+constexpr int kGroupTiles = 4; // n-tiles handled together by one task (64 output features)
+constexpr int kGroupRows = kTileN * kGroupTiles;
+constexpr int kMaxR = 32;
+constexpr int kTargetTasks = 768;  // about three tasks per compute unit of a 256-CU part
+constexpr int kMaxSplits = 16;
+constexpr int kGemmWaves = 4;      // wavefronts per GEMM workgroup
+constexpr int kAttnWaves = 4;
+constexpr int kKvBlock = 16;
+
+// One matrix in tile order: [Nt n-tiles][Ks k-steps][64 lanes][8 bf16]; lane l of tile (t, s)
+// holds row 16t + l%16, columns 32s + 8*(l/16) .. +8.  Rows / columns beyond N / K are zero.
+struct MatDesc {
+    size_t off;  // byte offset inside the packed blob (layer matrices: relative to the layer base)
+    int32_t N, K, Nt, Ks;
+    size_t bytes() const { return size_t(Nt) * Ks * 1024; }
+};
+
+struct GemmPlan {
+    int32_t groups;           // ceil(Nt / 4)
+    int32_t splits;           // cuts of the contraction dimension across workgroups
+    int32_t steps_per_split;  // k-steps per cut
+};
+
+struct Layout {
+    bool ok;
+    // packed weights
+    size_t embed_off, lm_off, g_final_off, layer0_off, layer_stride, weight_bytes;
+    MatDesc qkv, wo, gu, wd, lm;  // layer matrices relative to the layer base; lm absolute
+    size_t g_attn_off, g_ffn_off; // relative to the layer base
+    GemmPlan p_qkv, p_wo, p_gu, p_wd, p_lm;
+    // workspace (byte offsets)
+    size_t x_off, q_off, att_off, act_off, ss_off, part_off, cnt_off, apart_off, acnt_off, amax_off,
+        aidx_off, rope_off, ws_bytes;
+    int32_t ss_groups;   // rows of the sum-of-squares partial table
+    int32_t n_counters;  // int32 counters for split-K groups
+    int32_t attn_max_splits, attn_row_tiles_max;
+};
+
+inline int32_t ceil_div(int64_t a, int64_t b) { return int32_t((a + b - 1) / b); }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline GemmPlan plan_gemm(const MatDesc& m) {
+    GemmPlan p;
+    p.groups = ceil_div(m.Nt, kGroupTiles);
+    int32_t want = ceil_div(kTargetTasks, p.groups);
+    int32_t max_by_k = m.Ks / kGemmWaves;  // keep at least one k-step per wavefront
+    if (max_by_k < 1) max_by_k = 1;
+    int32_t s = want;
+    if (s > kMaxSplits) s = kMaxSplits;
+    if (s > max_by_k) s = max_by_k;
+    if (s < 1) s = 1;
+    p.steps_per_split = ceil_div(m.Ks, s);
+    p.splits = ceil_div(m.Ks, p.steps_per_split);
+    return p;
+}
+
+inline MatDesc make_mat(size_t off, int32_t N, int32_t K) {
+    MatDesc m;
+    m.off = off;
+    m.N = N;
+    m.K = K;
+    m.Nt = ceil_div(N, kTileN);
+    m.Ks = ceil_div(K, kTileK);
+    return m;
+}
+
+inline bool cfg_valid(const card_model_cfg* c) {
+    if (!c) return false;
+    if (c->n_layers <= 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->d_ffn <= 0 ||
+        c->vocab <= 1)
+        return false;
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->d_model % 64 || c->d_ffn % 8) return false;
+    if (c->n_q_heads % c->n_kv_heads) return false;
+    if (c->kv_block != kKvBlock) return false;
+    if (c->max_ctx <= 0 || c->max_ctx % kKvBlock) return false;
+    if (c->max_r < 1 || c->max_r > kMaxR) return false;
+    if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return false;
+    return true;
+}
+
+inline Layout make_layout(const card_model_cfg* c) {
+    Layout L = {};
+    if (!cfg_valid(c)) return L;
+    const int32_t d = c->d_model, h = c->head_dim, qd = c->n_q_heads * h, kvd = c->n_kv_heads * h;
+    size_t off = 0;
+    L.embed_off = off;
+    off = align_up(off + size_t(c->vocab) * d * 2, 1024);
+    L.lm = make_mat(off, c->vocab, d);
+    L.lm_off = off;
+    off = align_up(off + L.lm.bytes(), 1024);
+    L.g_final_off = off;
+    off = align_up(off + size_t(d) * 4, 1024);
+    L.layer0_off = off;
+    size_t lo = 0;
+    L.qkv = make_mat(lo, qd + 2 * kvd, d);
+    lo += L.qkv.bytes();
+    L.wo = make_mat(lo, d, qd);
+    lo += L.wo.bytes();
+    L.gu = make_mat(lo, 2 * c->d_ffn, d);
+    lo += L.gu.bytes();
+    L.wd = make_mat(lo, d, c->d_ffn);
+    lo += L.wd.bytes();
+    L.g_attn_off = lo;
+    lo = align_up(lo + size_t(d) * 4, 1024);
+    L.g_ffn_off = lo;
+    lo = align_up(lo + size_t(d) * 4, 1024);
+    L.layer_stride = lo;
+    L.weight_bytes = L.layer0_off + size_t(c->n_layers) * L.layer_stride;
+    L.p_qkv = plan_gemm(L.qkv);
+    L.p_wo = plan_gemm(L.wo);
+    L.p_gu = plan_gemm(L.gu);
+    L.p_wd = plan_gemm(L.wd);
+    L.p_lm = plan_gemm(L.lm);
+    L.p_lm.splits = 1;  // the vocabulary head has thousands of groups; never cut its K
+    L.p_lm.steps_per_split = L.lm.Ks;
+
+    // workspace
+    size_t w = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = w;
+        w = align_up(w + bytes, 256);
+        return at;
+    };
+    L.x_off = take(size_t(kMaxR) * d * 4);
+    L.q_off = take(size_t(kMaxR) * qd * 4);
+    L.att_off = take(size_t(kMaxR) * qd * 4);
+    L.act_off = take(size_t(kMaxR) * c->d_ffn * 4);
+    L.ss_groups = ceil_div(d, kGroupRows);
+    L.ss_off = take(size_t(L.ss_groups) * kMaxR * 4);
+    size_t part_floats = 0;
+    int32_t counters = 0;
+    const GemmPlan* plans[4] = {&L.p_qkv, &L.p_wo, &L.p_gu, &L.p_wd};
+    for (const GemmPlan* p : plans) {
+        size_t f = size_t(p->groups) * p->splits * kGroupRows * kMaxR;
+        if (p->splits > 1 && f > part_floats) part_floats = f;
+        if (p->groups > counters) counters = p->groups;
+    }
+    L.part_off = take(part_floats * 4);
+    L.n_counters = counters;
+    L.cnt_off = take(size_t(counters) * 4);
+    // attention partials: per (kv head, row-tile pair, split): M[32], L[32], O[32][h]
+    const int32_t G = c->n_q_heads / c->n_kv_heads;
+    L.attn_row_tiles_max = ceil_div(G * kMaxR, 16);
+    const int32_t pairs = ceil_div(L.attn_row_tiles_max, 2);
+    L.attn_max_splits = 64;
+    L.apart_off = take(size_t(c->n_kv_heads) * pairs * L.attn_max_splits * 32 * (h + 2) * 4);
+    L.acnt_off = take(size_t(c->n_kv_heads) * pairs * 4);
+    L.amax_off = take(size_t(L.p_lm.groups) * kMaxR * 4);
+    L.aidx_off = take(size_t(L.p_lm.groups) * kMaxR * 4);
+    L.rope_off = take(size_t(kMaxR) * h * 4);  // cos[32][h/2] then sin[32][h/2]
+    L.ws_bytes = w;
+    L.ok = true;
+    return L;
+}
+
+}  // namespace card

@@ -1,0 +1,141 @@
+"""Device-buffer plumbing around the C ABI: torch allocates, libcard computes."""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+def make_cfg(shape, max_ctx: int, max_r: int = 32) -> B.CardModelCfg:
+    """shape: any object with the ModelShape fields."""
+    max_ctx = (max_ctx + 15) // 16 * 16
+    return B.CardModelCfg(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                          shape.d_ffn, shape.vocab, shape.rope_theta, shape.rms_eps, 16, max_ctx, max_r)
+
+
+def _check(st: int, where: str) -> None:
+    if st != B.CARD_OK:
+        raise B.CardError(st, where)
+
+
+class Target:
+    """The target model's device state: packed weights, workspace, paged KV cache."""
+
+    def __init__(self, shape, max_ctx: int, max_r: int = 32, device: str = "cuda:0",
+                 page_order: Optional[Sequence[int]] = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("libcard needs a GPU: there is no CPU path")
+        self.device = torch.device(device)
+        self.cfg = make_cfg(shape, max_ctx, max_r)
+        wbytes = B.card_packed_weight_bytes(self.cfg)
+        if wbytes == 0:
+            raise B.CardError(B.CARD_EINVAL, "card_packed_weight_bytes")
+        self.packed = torch.empty(wbytes, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.zeros(B.card_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        self.n_pages = self.cfg.max_ctx // 16
+        pool = B.card_kv_pool_bytes(self.cfg, self.n_pages)
+        self.k_pages = torch.zeros(pool, dtype=torch.uint8, device=self.device)
+        self.v_pages = torch.zeros(pool, dtype=torch.uint8, device=self.device)
+        order = list(range(self.n_pages)) if page_order is None else [int(p) for p in page_order]
+        assert sorted(order) == list(range(self.n_pages))
+        self.block_table = torch.tensor(order, dtype=torch.int32, device=self.device)
+        self.out = torch.zeros(4, dtype=torch.int32, device=self.device)
+        self.row_argmax = torch.zeros(32, dtype=torch.int32, device=self.device)
+        self.cand = torch.zeros(32, dtype=torch.int32, device=self.device)
+
+    # -- weights
+    def pack(self, name: str, layer: int, src: torch.Tensor) -> None:
+        src = src.to(self.device).contiguous()
+        st = B.card_weights_pack_tensor(self.cfg, B.TENSOR_IDS[name], layer, src, self.packed, self._stream())
+        _check(st, f"card_weights_pack_tensor({name}, {layer})")
+        torch.cuda.current_stream(self.device).synchronize()  # src may be freed by the caller
+
+    def _stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def kv(self, pending: int) -> B.CardKV:
+        return B.CardKV(self.k_pages.data_ptr(), self.v_pages.data_ptr(), self.block_table.data_ptr(),
+                        self.n_pages, int(pending))
+
+    # -- one verification step
+    def enqueue_verify(self, ctx_len: int, pending: int, r: int, logits: Optional[torch.Tensor] = None) -> int:
+        """Enqueue on the current stream using the tokens already in self.cand[:r]; no sync."""
+        kv = self.kv(pending)
+        if logits is None:
+            return B.card_verify(self.cfg, self.packed, kv, ctx_len, self.cand, r, self.workspace,
+                                 self._stream(), self.out, self.row_argmax)
+        return B.card_verify_debug_logits(self.cfg, self.packed, kv, ctx_len, self.cand, r, self.workspace,
+                                          self._stream(), self.out, self.row_argmax, logits)
+
+    def verify(self, ctx_len: int, pending: int, cand: Sequence[int], want_logits: bool = False) -> Dict:
+        r = len(cand)
+        if 0 < r <= 32:
+            self.cand[:r] = torch.tensor([int(c) for c in cand], dtype=torch.int32, device=self.device)
+        logits = None
+        if want_logits:
+            logits = torch.empty((max(r, 1), self.cfg.vocab), dtype=torch.float32, device=self.device)
+        _check(self.enqueue_verify(ctx_len, pending, r, logits), "card_verify")
+        torch.cuda.current_stream(self.device).synchronize()
+        o = self.out.tolist()
+        res = {"accepted_len": o[0], "correction_token": o[1], "kv_first_slot": o[2], "kv_count": o[3],
+               "row_argmax": self.row_argmax[:r].tolist()}
+        if want_logits:
+            res["logits"] = logits.cpu()
+        return res
+
+    def prefill(self, tokens: Sequence[int], chunk: int = 32) -> int:
+        """Build KV[0:n) with verify calls that carry no pending token; returns the arg-max after
+        the last context token (the pending prediction g0)."""
+        chunk = min(chunk, self.cfg.max_r)
+        last = None
+        for s in range(0, len(tokens), chunk):
+            last = self.verify(s, -1, tokens[s:s + chunk])
+        return last["row_argmax"][-1]
+
+    def kv_gather(self, layer: int, first: int, count: int):
+        shp = (count, self.cfg.n_kv_heads, self.cfg.head_dim)
+        k = torch.empty(shp, dtype=torch.float32, device=self.device)
+        v = torch.empty(shp, dtype=torch.float32, device=self.device)
+        _check(B.card_kv_gather(self.cfg, self.kv(-1), layer, first, count, k, v, self._stream()), "card_kv_gather")
+        torch.cuda.current_stream(self.device).synchronize()
+        return k.cpu(), v.cpu()
+
+
+class CandidateCache:
+    """RAII wrapper of the host-side shared candidate cache."""
+
+    def __init__(self, K: int, max_depth: int):
+        st, self.h = B.card_cache_create(K, max_depth)
+        _check(st, "card_cache_create")
+        self.K = K
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            B.card_cache_destroy(self.h)
+            self.h = None
+
+    def write(self, level: int, tokens, parents, scores, epoch: Optional[int] = None) -> int:
+        return B.card_cache_write(self.h, self.epoch() if epoch is None else epoch, level, tokens, parents, scores)
+
+    def query(self, token: int, max_len: int):
+        st, toks, score = B.card_cache_query(self.h, token, max_len)
+        if st < 0:
+            raise B.CardError(st, "card_cache_query")
+        return bool(st), toks, score
+
+    def correct(self, tokens) -> bool:
+        st = B.card_cache_correct(self.h, tokens)
+        if st < 0:
+            raise B.CardError(st, "card_cache_correct")
+        return bool(st)
+
+    def epoch(self) -> int:
+        return B.card_cache_epoch(self.h)
+
+    def depth(self) -> int:
+        return B.card_cache_depth(self.h)
+
+    def level(self, l: int):
+        return B.card_cache_read_level(self.h, l, self.K)
