@@ -99,6 +99,7 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
         e.n_counters = L.n_counters;
         e.acounters = acnt;
         e.n_acounters = cfg->n_kv_heads * ceil_div(L.attn_row_tiles_max, 2);
+        e.best = reinterpret_cast<unsigned long long*>(ws + L.best_off);
         hipLaunchKernelGGL(k_embed, dim3(d / 64), dim3(64), 0, st, e);
         if (launch_status() != CARD_OK) return CARD_EDEVICE;
     }
@@ -184,23 +185,20 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
         a.ss_in_groups = L.ss_groups;
         a.inv_d = inv_d;
         a.eps = cfg->rms_eps;
-        a.amax = reinterpret_cast<float*>(ws + L.amax_off);
-        a.aidx = reinterpret_cast<int32_t*>(ws + L.aidx_off);
+        a.best = reinterpret_cast<unsigned long long*>(ws + L.best_off);
         a.logits = logits;
         if (gemm(EPI_LMHEAD, r, a, L.p_lm, st) != CARD_OK) return CARD_EDEVICE;
     }
     {
         AcceptArgs a = {};
-        a.amax = reinterpret_cast<const float*>(ws + L.amax_off);
-        a.aidx = reinterpret_cast<const int32_t*>(ws + L.aidx_off);
-        a.groups = L.p_lm.groups;
+        a.best = reinterpret_cast<const unsigned long long*>(ws + L.best_off);
         a.r = r;
         a.cand = cand;
         a.pending = kv->pending_token;
         a.ctx_len = ctx_len;
         a.out = out;
         a.row_argmax = row_argmax;
-        hipLaunchKernelGGL(k_accept, dim3(1), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, st, a);
         if (launch_status() != CARD_OK) return CARD_EDEVICE;
     }
     return CARD_OK;

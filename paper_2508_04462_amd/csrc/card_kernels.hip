@@ -47,10 +47,30 @@ struct GemmArgs {
     int32_t ctx_len, head_dim, q_dim, kv_dim, n_kv_heads;
     float* act;           // SWIGLU: [r][F]
     int32_t F;
-    float* amax;          // LMHEAD: [groups][32]
-    int32_t* aidx;
+    unsigned long long* best;  // LMHEAD: [32] packed (logit key, ~index), zero on entry
     float* logits;        // LMHEAD debug: [r][N] or nullptr
 };
+
+// Data handed from one workgroup to another inside a kernel goes through agent-scope relaxed
+// atomics: the store writes through the compute die's own L2, the load bypasses it.  That is
+// enough for the "last workgroup to arrive merges" hand-off and costs far less than a full
+// device fence (which writes back and invalidates the whole L2 on every call).
+__device__ __forceinline__ void st_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// all of this thread's earlier stores have been acknowledged
+__device__ __forceinline__ void wait_stores() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+}
+// order-preserving map float -> uint32 (larger float, larger key)
+__device__ __forceinline__ uint32_t float_key(float v) {
+    const uint32_t b = __float_as_uint(v);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
 
 __device__ __forceinline__ void split_bf16(float v, __bf16& hi, __bf16& lo) {
     hi = static_cast<__bf16>(v);
@@ -76,10 +96,16 @@ __global__ __launch_bounds__(kGemmWaves * 64) void k_gemm(GemmArgs a) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int group = blockIdx.x / a.splits, split = blockIdx.x % a.splits;
 
-    if (EPI != EPI_RESID && tid < a.r) {
+    if (EPI != EPI_RESID) {
+        // eight lanes per row add the per-group sums of squares (fixed order), then a butterfly
+        const int mrow = tid >> 3, sub = tid & 7;
         float ss = 0.f;
-        for (int g = 0; g < a.ss_in_groups; ++g) ss += a.ss_in[g * kMaxR + tid];
-        row_scale[tid] = 1.0f / sqrtf(ss * a.inv_d + a.eps);
+        if (mrow < a.r)
+            for (int g = sub; g < a.ss_in_groups; g += 8) ss += a.ss_in[g * kMaxR + mrow];
+        ss += __shfl_xor(ss, 1);
+        ss += __shfl_xor(ss, 2);
+        ss += __shfl_xor(ss, 4);
+        if (sub == 0 && mrow < a.r) row_scale[mrow] = 1.0f / sqrtf(ss * a.inv_d + a.eps);
     }
 
     const int ks0 = split * a.steps_per_split;
@@ -184,24 +210,27 @@ __global__ __launch_bounds__(kGemmWaves * 64) void k_gemm(GemmArgs a) {
 
     if (a.splits > 1) {
         float* mine = a.part + (size_t(group) * a.splits + split) * (kGroupRows * COLS);
-        for (int e = tid; e < kGroupRows * COLS; e += kGemmWaves * 64) mine[e] = tile[e];
-        __threadfence();
+        for (int e = tid; e < kGroupRows * COLS; e += kGemmWaves * 64) st_agent(mine + e, tile[e]);
+        wait_stores();
         __syncthreads();
         if (tid == 0) {
-            const int prev = atomicAdd(&a.counters[group], 1);
+            const int prev = __hip_atomic_fetch_add(&a.counters[group], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             is_last = (prev == a.splits - 1);
         }
         __syncthreads();
         if (!is_last) return;
-        __threadfence();
         const float* base = a.part + size_t(group) * a.splits * (kGroupRows * COLS);
         for (int e = tid; e < kGroupRows * COLS; e += kGemmWaves * 64) {
+            float pv[kMaxSplits];
+#pragma unroll
+            for (int sp = 0; sp < kMaxSplits; ++sp)
+                pv[sp] = sp < a.splits ? ld_agent(base + size_t(sp) * (kGroupRows * COLS) + e) : 0.f;
             float s = 0.f;
-            for (int sp = 0; sp < a.splits; ++sp)
-                s += __builtin_nontemporal_load(base + size_t(sp) * (kGroupRows * COLS) + e);
+#pragma unroll
+            for (int sp = 0; sp < kMaxSplits; ++sp) s += pv[sp];
             tile[e] = s;
         }
-        if (tid == 0) a.counters[group] = 0;
+        if (tid == 0) __hip_atomic_store(&a.counters[group], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
     }
 
@@ -259,8 +288,10 @@ __global__ __launch_bounds__(kGemmWaves * 64) void k_gemm(GemmArgs a) {
                     bi = row0 + nl;
                 }
             }
-            a.amax[group * kMaxR + tid] = best;
-            a.aidx[group * kMaxR + tid] = bi;
+            // (value, lowest index) as one 64-bit key; the maximum does not depend on arrival order
+            const unsigned long long key =
+                (static_cast<unsigned long long>(float_key(best)) << 32) | (0xffffffffu - uint32_t(bi));
+            __hip_atomic_fetch_max(&a.best[tid], key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     } else {  // EPI_QKV
         // packed rows: [q heads | k heads | v heads]; inside a q or k head row 2p holds element p
@@ -323,6 +354,7 @@ struct EmbedArgs {
     int32_t n_counters;
     int32_t* acounters;
     int32_t n_acounters;
+    unsigned long long* best;  // [32] arg-max keys, cleared here
 };
 
 __global__ __launch_bounds__(64) void k_embed(EmbedArgs a) {
@@ -341,17 +373,17 @@ __global__ __launch_bounds__(64) void k_embed(EmbedArgs a) {
         for (int o = 32; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
         if (lane == 0) a.ss_out[g * kMaxR + m] = ss;
     }
-    if (g == 0) {
-        const int half = a.head_dim >> 1;
-        for (int e = lane; e < a.r * half; e += 64) {
-            const int m = e / half, j = e % half;
-            const double ang = double(a.ctx_len + m) * pow(double(a.theta), -2.0 * j / a.head_dim);
-            a.rope[m * half + j] = float(cos(ang));
-            a.rope[kMaxR * half + m * half + j] = float(sin(ang));
-        }
-        for (int e = lane; e < a.n_counters; e += 64) a.counters[e] = 0;
-        for (int e = lane; e < a.n_acounters; e += 64) a.acounters[e] = 0;
+    // rotation table, spread over the workgroups; angles in fp64 so long contexts stay exact
+    const int half = a.head_dim >> 1;
+    for (int e = n; e < a.r * half; e += gridDim.x * 64) {
+        const int m = e / half, j = e % half;
+        const double ang = double(a.ctx_len + m) * pow(double(a.theta), -2.0 * j / a.head_dim);
+        a.rope[m * half + j] = float(cos(ang));
+        a.rope[kMaxR * half + m * half + j] = float(sin(ang));
     }
+    for (int e = n; e < a.n_counters; e += gridDim.x * 64) a.counters[e] = 0;
+    for (int e = n; e < a.n_acounters; e += gridDim.x * 64) a.acounters[e] = 0;
+    if (n < kMaxR) a.best[n] = 0ull;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -524,34 +556,39 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs a) {
         const int row = e / H;
         float acc = 0.f;
         for (int w = 0; w < kAttnWaves; ++w) acc += wgt[w * 32 + row] * lds[w * PART + 64 + e];
-        gpart[64 + e] = acc;
+        st_agent(gpart + 64 + e, acc);
     }
     if (tid < 32) {
-        gpart[tid] = wgt[kAttnWaves * 32 + tid];
-        gpart[32 + tid] = wgt[(kAttnWaves + 1) * 32 + tid];
+        st_agent(gpart + tid, wgt[kAttnWaves * 32 + tid]);
+        st_agent(gpart + 32 + tid, wgt[(kAttnWaves + 1) * 32 + tid]);
     }
-    __threadfence();
+    wait_stores();
     __syncthreads();
     const int cidx = kvh * a.row_pairs + pair;
     if (tid == 0) {
-        const int prev = atomicAdd(&a.counters[cidx], 1);
+        const int prev = __hip_atomic_fetch_add(&a.counters[cidx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         is_last = (prev == a.splits - 1);
     }
     __syncthreads();
     if (!is_last) return;
-    __threadfence();
     const float* base = a.part + size_t(blockIdx.x - split) * PART;
-    // merge the cuts in cut order
+    // merge the cuts in cut order: one thread per (row, cut) fetches max and sum, then per row
+    for (int e = tid; e < 32 * a.splits; e += kAttnWaves * 64) {
+        const int row = e & 31, sp = e >> 5;
+        lds[e] = ld_agent(base + size_t(sp) * PART + row);
+        lds[2048 + e] = ld_agent(base + size_t(sp) * PART + 32 + row);
+    }
+    __syncthreads();
     if (tid < 32) {
         float mg = -1e30f;
-        for (int sp = 0; sp < a.splits; ++sp) mg = fmaxf(mg, __builtin_nontemporal_load(base + size_t(sp) * PART + tid));
+        for (int sp = 0; sp < a.splits; ++sp) mg = fmaxf(mg, lds[sp * 32 + tid]);
         float l = 0.f;
         for (int sp = 0; sp < a.splits; ++sp) {
-            const float f = expf(__builtin_nontemporal_load(base + size_t(sp) * PART + tid) - mg);
-            if (sp < 64) wgt[sp * 32 + tid] = f;
-            l += f * __builtin_nontemporal_load(base + size_t(sp) * PART + 32 + tid);
+            const float f = expf(lds[sp * 32 + tid] - mg);
+            wgt[sp * 32 + tid] = f;
+            l += f * lds[2048 + sp * 32 + tid];
         }
-        lds[tid] = l;
+        lds[4096 + tid] = l;
     }
     __syncthreads();
     for (int e = tid; e < 32 * H; e += kAttnWaves * 64) {
@@ -559,12 +596,22 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs a) {
         const int rho = pair * 32 + row;
         if (rho >= R) continue;
         float acc = 0.f;
-        for (int sp = 0; sp < a.splits; ++sp)
-            acc += wgt[sp * 32 + row] * __builtin_nontemporal_load(base + size_t(sp) * PART + 64 + e);
+        int sp = 0;
+        for (; sp + 4 <= a.splits; sp += 4) {
+            const float v0 = ld_agent(base + size_t(sp) * PART + 64 + e);
+            const float v1 = ld_agent(base + size_t(sp + 1) * PART + 64 + e);
+            const float v2 = ld_agent(base + size_t(sp + 2) * PART + 64 + e);
+            const float v3 = ld_agent(base + size_t(sp + 3) * PART + 64 + e);
+            acc += wgt[sp * 32 + row] * v0;
+            acc += wgt[(sp + 1) * 32 + row] * v1;
+            acc += wgt[(sp + 2) * 32 + row] * v2;
+            acc += wgt[(sp + 3) * 32 + row] * v3;
+        }
+        for (; sp < a.splits; ++sp) acc += wgt[sp * 32 + row] * ld_agent(base + size_t(sp) * PART + 64 + e);
         const int m = rho / a.G, gl = rho % a.G;
-        a.att[size_t(m) * a.q_dim + (kvh * a.G + gl) * H + hh] = acc / lds[row];
+        a.att[size_t(m) * a.q_dim + (kvh * a.G + gl) * H + hh] = acc / lds[4096 + row];
     }
-    if (tid == 0) a.counters[cidx] = 0;
+    if (tid == 0) __hip_atomic_store(&a.counters[cidx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -572,48 +619,19 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs a) {
 // (overview figure: accept the matching prefix, emit the target's own next token).
 // ------------------------------------------------------------------------------------------
 struct AcceptArgs {
-    const float* amax;
-    const int32_t* aidx;
-    int32_t groups, r;
+    const unsigned long long* best;  // [32] packed (logit key, ~index) per row
+    int32_t r;
     const int32_t* cand;
     int32_t pending, ctx_len;
     card_verify_result* out;
     int32_t* row_argmax;  // optional
 };
 
-__global__ __launch_bounds__(256) void k_accept(AcceptArgs a) {
-    __shared__ float bv[256];
-    __shared__ int bi[256];
+__global__ __launch_bounds__(64) void k_accept(AcceptArgs a) {
     __shared__ int pred[kMaxR + 1];
     const int tid = threadIdx.x;
-    for (int m = 0; m < a.r; ++m) {
-        float best = -INFINITY;
-        int idx = 0x7fffffff;
-        for (int g = tid; g < a.groups; g += 256) {
-            const float v = a.amax[g * kMaxR + m];
-            const int i = a.aidx[g * kMaxR + m];
-            if (v > best || (v == best && i < idx)) {
-                best = v;
-                idx = i;
-            }
-        }
-        bv[tid] = best;
-        bi[tid] = idx;
-        __syncthreads();
-        for (int o = 128; o >= 1; o >>= 1) {
-            if (tid < o) {
-                const float v = bv[tid + o];
-                const int i = bi[tid + o];
-                if (v > bv[tid] || (v == bv[tid] && i < bi[tid])) {
-                    bv[tid] = v;
-                    bi[tid] = i;
-                }
-            }
-            __syncthreads();
-        }
-        if (tid == 0) pred[m + 1] = bi[0];
-        __syncthreads();
-    }
+    if (tid < a.r) pred[tid + 1] = int(0xffffffffu - uint32_t(a.best[tid] & 0xffffffffull));
+    __syncthreads();
     if (tid == 0) {
         pred[0] = a.pending < 0 ? a.cand[0] : a.pending;
         int j = 0;

@@ -41,8 +41,8 @@ struct Layout {
     size_t g_attn_off, g_ffn_off; // relative to the layer base
     GemmPlan p_qkv, p_wo, p_gu, p_wd, p_lm;
     // workspace (byte offsets)
-    size_t x_off, q_off, att_off, act_off, ss_off, part_off, cnt_off, apart_off, acnt_off, amax_off,
-        aidx_off, rope_off, ws_bytes;
+    size_t x_off, q_off, att_off, act_off, ss_off, part_off, cnt_off, apart_off, acnt_off, best_off,
+        rope_off, ws_bytes;
     int32_t ss_groups;   // rows of the sum-of-squares partial table
     int32_t n_counters;  // int32 counters for split-K groups
     int32_t attn_max_splits, attn_row_tiles_max;
@@ -158,8 +158,7 @@ inline Layout make_layout(const card_model_cfg* c) {
     L.attn_max_splits = 64;
     L.apart_off = take(size_t(c->n_kv_heads) * pairs * L.attn_max_splits * 32 * (h + 2) * 4);
     L.acnt_off = take(size_t(c->n_kv_heads) * pairs * 4);
-    L.amax_off = take(size_t(L.p_lm.groups) * kMaxR * 4);
-    L.aidx_off = take(size_t(L.p_lm.groups) * kMaxR * 4);
+    L.best_off = take(size_t(kMaxR) * 8);
     L.rope_off = take(size_t(kMaxR) * h * 4);  // cos[32][h/2] then sin[32][h/2]
     L.ws_bytes = w;
     L.ok = true;

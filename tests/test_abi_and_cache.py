@@ -1,0 +1,165 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, sizes and
+argument errors come from host code, and the host-side candidate cache agrees with its oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import card_inputs as ci
+import paper_2508_04462_amd as card
+from oracle.cache_oracle import CandidateCacheOracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "card.h")).read()
+    names = set(re.findall(r"\b(card_[a-z_]+)\s*\(", header))
+    assert {"card_verify", "card_cache_query", "card_cache_write", "card_cache_correct"} <= names
+    for n in sorted(names):
+        assert hasattr(card.lib, n), n
+
+
+def test_sizes_follow_the_shapes():
+    shape = ci.SHAPES["llama8b"]
+    cfg = card.make_cfg(shape, 2048)
+    wb = card.card_packed_weight_bytes(cfg)
+    # streamed bf16 weights + the embedding table + gains, a little tile padding
+    expect = shape.streamed_weight_bytes() + 2 * shape.vocab * shape.d_model
+    assert expect <= wb <= expect * 1.001
+    assert card.card_kv_pool_bytes(cfg, 128) == 32 * 128 * 8 * 16 * 128 * 2
+    assert card.card_workspace_bytes(cfg) > 32 * 4096 * 4
+    bad = card.make_cfg(shape, 2048)
+    bad.head_dim = 96
+    assert card.card_packed_weight_bytes(bad) == 0 and card.card_workspace_bytes(bad) == 0
+
+
+def test_argument_errors_are_caught_on_the_host():
+    cfg = card.make_cfg(ci.SHAPES["tiny"], 256)
+    kv = card.CardKV(0x1000, 0x1000, 0x1000, 16, -1)
+    assert card.card_verify(cfg, None, kv, 0, 0x1000, 1, 0x1000, None, 0x1000) == card.CARD_EINVAL
+    assert card.card_verify(cfg, 0x1000, kv, 0, 0x1000, 0, 0x1000, None, 0x1000) == card.CARD_ERANGE
+    assert card.card_verify(cfg, 0x1000, kv, 0, 0x1000, 33, 0x1000, None, 0x1000) == card.CARD_ERANGE
+    assert card.card_verify(cfg, 0x1000, kv, 250, 0x1000, 8, 0x1000, None, 0x1000) == card.CARD_ECAPACITY
+    assert card.card_verify(cfg, 0x1000, kv, -1, 0x1000, 8, 0x1000, None, 0x1000) == card.CARD_EINVAL
+    assert card.card_weights_pack_tensor(cfg, 99, 0, 0x1000, 0x1000) == card.CARD_EINVAL
+    assert card.card_weights_pack_tensor(cfg, card.TENSOR_IDS["wq"], 7, 0x1000, 0x1000) == card.CARD_ERANGE
+    assert card.card_strerror(card.CARD_ECAPACITY) == "KV cache capacity exceeded"
+
+
+# ------------------------------------------------------------------------------- candidate cache
+
+
+def _random_tree(rng, K, depth, vocab):
+    levels = []
+    prev = 0
+    for l in range(depth):
+        n = int(rng.integers(1, K + 1))
+        toks = rng.integers(0, vocab, size=n).tolist()
+        parents = [-1] * n if l == 0 else rng.integers(0, prev, size=n).tolist()
+        scores = (rng.integers(1, 64, size=n) / 64.0).tolist()  # exact in fp32, ties happen
+        levels.append((toks, parents, scores))
+        prev = n
+    return levels
+
+
+def _same(lib_cache, ora):
+    assert lib_cache.depth() == ora.depth()
+    for l, lv in enumerate(ora.levels):
+        n, t, p, s = lib_cache.level(l)
+        assert (n, t, p) == (len(lv.tokens), lv.tokens, lv.parents)
+        np.testing.assert_allclose(s, lv.scores)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_cache_matches_oracle_on_random_trees(seed):
+    rng = np.random.default_rng(seed)
+    K, depth, vocab = 6, 5, 7  # a tiny vocabulary forces duplicate tokens
+    c = card.CandidateCache(K, depth)
+    o = CandidateCacheOracle(K, depth)
+    for _ in range(6):
+        for l, (t, p, s) in enumerate(_random_tree(rng, K, depth, vocab)):
+            assert c.write(l, t, p, s) == card.CARD_OK
+            o.write_level(l, t, p, s)
+        _same(c, o)
+        for tok in range(vocab):
+            for max_len in (1, 2, 3, 9):
+                hit, path, score = c.query(tok, max_len)
+                ohit, opath, oscore = o.query(tok, max_len)
+                assert (hit, path) == (ohit, opath)
+                assert abs(score - oscore) < 1e-6
+        # walk a verified chain that mostly follows the tree and sometimes leaves it
+        chain = []
+        node_tok = o.levels[0].tokens[int(rng.integers(len(o.levels[0].tokens)))]
+        hit, path, _ = o.query(node_tok, int(rng.integers(1, depth + 1)))
+        chain = list(path)
+        if rng.random() < 0.3:
+            chain.append(vocab + 1)
+        assert c.correct(chain) == o.correct(chain)
+        _same(c, o)
+        assert c.epoch() == o.epoch
+        # refill below what is left, as the draft side would
+        base = o.depth()
+        for l in range(base, depth):
+            n_prev = len(o.levels[l - 1].tokens) if l else 0
+            n = int(rng.integers(1, K + 1))
+            t = rng.integers(0, vocab, size=n).tolist()
+            p = [-1] * n if l == 0 else rng.integers(0, n_prev, size=n).tolist()
+            s = (rng.integers(1, 64, size=n) / 64.0).tolist()
+            assert c.write(l, t, p, s) == card.CARD_OK
+            o.write_level(l, t, p, s)
+        _same(c, o)
+
+
+def test_cache_write_errors_and_stale_epoch():
+    c = card.CandidateCache(4, 3)
+    assert c.write(1, [1], [0], [0.5]) == card.CARD_ERANGE  # level 0 missing
+    assert c.write(0, [1, 2], [-1, -1], [0.6, 0.4]) == card.CARD_OK
+    assert c.write(0, [1, 2], [0, -1], [0.6, 0.4]) == card.CARD_ERANGE  # level-0 parents must be -1
+    assert c.write(1, [3], [2], [0.5]) == card.CARD_ERANGE  # parent outside level 0
+    assert c.write(1, [1, 2, 3, 4, 5], [0] * 5, [0.1] * 5) == card.CARD_ERANGE  # more than K nodes
+    assert c.write(1, [3], [1], [0.5]) == card.CARD_OK
+    assert c.write(3, [3], [0], [0.5]) == card.CARD_ERANGE  # beyond max_depth
+    e = c.epoch()
+    assert c.correct([2])
+    assert c.write(1, [9], [0], [0.5], epoch=e) == card.CARD_ESTALE  # the writer missed a correction
+    assert c.level(0)[1] == [3]
+    assert c.write(1, [9], [0], [0.5]) == card.CARD_OK
+
+
+def test_cache_concurrent_writer_and_reader_do_not_corrupt():
+    import threading
+
+    c = card.CandidateCache(8, 4)
+    stop = threading.Event()
+    errors = []
+
+    def writer():
+        rng = np.random.default_rng(0)
+        while not stop.is_set():
+            ep = c.epoch()
+            prev = 0
+            for l in range(4):
+                n = int(rng.integers(1, 9))
+                p = [-1] * n if l == 0 else rng.integers(0, prev, size=n).tolist()
+                st = c.write(l, rng.integers(0, 5, size=n).tolist(), p, rng.random(n).tolist(), epoch=ep)
+                if st == card.CARD_ESTALE:
+                    break
+                if st != card.CARD_OK:
+                    errors.append(st)
+                prev = n
+
+    th = threading.Thread(target=writer)
+    th.start()
+    try:
+        for i in range(3000):
+            hit, path, _ = c.query(i % 5, 4)
+            assert len(path) <= 4 and (not hit or path[0] == i % 5)
+            if i % 7 == 0:
+                c.correct(path[:2])
+    finally:
+        stop.set()
+        th.join()
+    assert not errors

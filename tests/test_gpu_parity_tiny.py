@@ -1,0 +1,166 @@
+"""GPU parity of the verify step against the CPU oracle, small shapes, element by element.
+
+All calls go through the C ABI (paper_2508_04462_amd.binding).  Bars:
+  * arg-max tokens, accepted_len, correction token: bit-exact wherever every deciding row's
+    top-1/top-2 gap in the oracle exceeds 0.05; otherwise the GPU token must be one of the
+    oracle's top two;
+  * final-layer logits: per row max|gpu - oracle| / max|oracle| <= 2e-2;
+  * K/V written to the paged cache: within bf16 rounding of the oracle's fp64 values.
+"""
+import numpy as np
+import pytest
+import torch
+
+import card_inputs as ci
+from oracle import card_oracle as co
+
+pytestmark = pytest.mark.gpu
+
+from gpu_common import GAP, logits_rel_err, make_pair  # noqa: E402
+
+TINY = ci.SHAPES["tiny"]
+# head_dim 128, G = 4, FFN not a multiple of 64, vocab not a multiple of 16, three layers
+MID = ci.ModelShape("mid", 3, 512, 8, 2, 128, 1048, 3001, ctx=200, r=8)
+
+
+def _check_rows(res, ref_logits):
+    """Arg-max per row: exact where decisive, else within the oracle's top two."""
+    n_decisive = 0
+    for i, row in enumerate(ref_logits):
+        top2 = np.argsort(row)[-2:][::-1]
+        if co.top2_gap(row) > GAP:
+            assert res["row_argmax"][i] == int(top2[0]), f"row {i}"
+            n_decisive += 1
+        else:
+            assert res["row_argmax"][i] in (int(top2[0]), int(top2[1])), f"row {i}"
+    return n_decisive
+
+
+@pytest.fixture(scope="module")
+def tiny_pair():
+    tgt, w = make_pair(TINY, seed=1, max_ctx=320, gain_jitter=0.25)
+    ctx = ci.uniform_tokens(1, "ctx_tokens", 0, TINY.ctx, TINY.vocab).tolist()
+    kv = co.OracleKV.empty(TINY, 320)
+    g0 = co.prefill(TINY, w, kv, ctx)
+    g0_gpu = tgt.prefill(ctx)
+    return tgt, w, ctx, kv, g0, g0_gpu
+
+
+def test_prefill_kv_matches_oracle(tiny_pair):
+    tgt, w, ctx, kv, g0, g0_gpu = tiny_pair
+    for l in range(TINY.n_layers):
+        k, v = tgt.kv_gather(l, 0, TINY.ctx)
+        ref_k, ref_v = kv.k[l][: TINY.ctx], kv.v[l][: TINY.ctx]
+        # bf16 keeps 8 significant bits: half an ulp is 2^-9 relative; layer 1 also carries the
+        # rounding of layer 0's cache
+        assert np.abs(k.numpy() - ref_k).max() <= 2.0 ** -8 * np.abs(ref_k).max()
+        assert np.abs(v.numpy() - ref_v).max() <= 2.0 ** -8 * np.abs(ref_v).max()
+
+
+def test_logits_and_argmax_random_candidates(tiny_pair):
+    tgt, w, ctx, kv, g0, g0_gpu = tiny_pair
+    cand = ci.uniform_tokens(1, "cand_tokens", 7, TINY.r, TINY.vocab).tolist()
+    res = tgt.verify(TINY.ctx, g0, cand, want_logits=True)
+    ref = co.forward_rows(TINY, w, kv, cand, TINY.ctx)
+    assert logits_rel_err(res["logits"], ref) <= 2e-2
+    _check_rows(res, ref)
+    assert res["kv_first_slot"] == TINY.ctx and res["kv_count"] == res["accepted_len"]
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
+def test_planted_prefix_all_j(seed):
+    """Workload recipe of the small configuration: 128 uniform context tokens, r = 4, the first j
+    candidates are the oracle's greedy tokens; every j in 0..4."""
+    shape = TINY
+    tgt, w = make_pair(shape, seed, max_ctx=160)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, shape.ctx, shape.vocab).tolist()
+    kv = co.OracleKV.empty(shape, 160)
+    g0 = co.prefill(shape, w, kv, ctx)
+    greedy, gaps = co.greedy_decode_cached(shape, w, kv, shape.ctx, g0, shape.r)
+    tgt.prefill(ctx)
+    checked = 0
+    for j in range(shape.r + 1):
+        cand = ci.plant_candidates(greedy, j, shape.r, shape.vocab, seed, stream=j)
+        ref = co.verify(shape, w, kv, shape.ctx, g0, cand, keep_logits=True)
+        assert ref.accepted_len == j
+        res = tgt.verify(shape.ctx, g0, cand, want_logits=True)
+        assert logits_rel_err(res["logits"], ref.logits) <= 2e-2
+        _check_rows(res, ref.logits)
+        # rows 0..j-2 decide the accepted prefix, row j-1 supplies the correction token
+        if all(g > GAP for g in ref.row_gap[:j]):
+            assert res["accepted_len"] == j
+            assert res["correction_token"] == ref.correction_token
+            assert (res["kv_first_slot"], res["kv_count"]) == (shape.ctx, j)
+            checked += 1
+    assert checked >= 1  # j = 0 never depends on a logit
+
+
+@pytest.mark.parametrize("r,ctx_len", [(1, 0), (1, 77), (3, 15), (16, 16), (17, 33), (32, 100), (5, 251)])
+def test_shapes_mid_model(r, ctx_len):
+    """Ragged context lengths around page boundaries, r on both sides of the 16-row tile, r = 1
+    (plain decode step), empty context."""
+    shape = MID
+    tgt, w = make_pair(shape, 11, max_ctx=288, gain_jitter=0.2)
+    toks = ci.uniform_tokens(11, "ctx_tokens", r, ctx_len + r, shape.vocab).tolist()
+    kv = co.OracleKV.empty(shape, 288)
+    if ctx_len:
+        co.prefill(shape, w, kv, toks[:ctx_len])
+        tgt.prefill(toks[:ctx_len], chunk=29)  # a chunk size that is neither 16 nor 32
+    ref = co.verify(shape, w, kv, ctx_len, -1, toks[ctx_len:], keep_logits=True)
+    res = tgt.verify(ctx_len, -1, toks[ctx_len:], want_logits=True)
+    assert logits_rel_err(res["logits"], ref.logits) <= 2e-2
+    _check_rows(res, ref.logits)
+    k, v = tgt.kv_gather(shape.n_layers - 1, 0, ctx_len + r)
+    ref_k = kv.k[-1][: ctx_len + r]
+    assert np.abs(k.numpy() - ref_k).max() <= 2.0 ** -7 * np.abs(ref_k).max()
+
+
+def test_chained_steps_reproduce_greedy_stream(tiny_pair):
+    """Several verify calls in a row, each starting from the previous result, emit exactly the
+    oracle's greedy continuation as long as the stream stays decisive."""
+    tgt, w, ctx, kv, g0, g0_gpu = tiny_pair
+    n_new = 12
+    kv_ref = co.OracleKV.empty(TINY, 320)
+    pending_ref = co.prefill(TINY, w, kv_ref, ctx)
+    want, gaps = co.greedy_decode_cached(TINY, w, kv_ref, TINY.ctx, pending_ref, n_new)
+    decisive_upto = next((i for i, g in enumerate(gaps) if g <= GAP), n_new)
+    tgt.prefill(ctx)
+    n, pending, emitted = TINY.ctx, g0_gpu, [g0_gpu]
+    step = 0
+    while len(emitted) <= decisive_upto and len(emitted) < n_new:
+        guess = want[len(emitted): len(emitted) + 3]
+        cand = [pending] + [g if (step + i) % 3 else (g + 1) % TINY.vocab for i, g in enumerate(guess)]
+        res = tgt.verify(n, pending, cand)
+        assert res["accepted_len"] >= 1
+        emitted += cand[1: res["accepted_len"]] + [res["correction_token"]]
+        n += res["kv_count"]
+        pending = res["correction_token"]
+        step += 1
+    k = min(len(emitted), decisive_upto + 1)
+    assert emitted[:k] == want[:k]
+
+
+def test_results_are_deterministic_run_to_run(tiny_pair):
+    tgt, w, ctx, kv, g0, g0_gpu = tiny_pair
+    cand = ci.uniform_tokens(1, "cand_tokens", 9, 8, TINY.vocab).tolist()
+    a = tgt.verify(TINY.ctx, g0, cand, want_logits=True)
+    b = tgt.verify(TINY.ctx, g0, cand, want_logits=True)
+    assert torch.equal(a["logits"], b["logits"]) and a["row_argmax"] == b["row_argmax"]
+
+
+def test_argument_errors_enqueue_nothing(tiny_pair):
+    import paper_2508_04462_amd as card
+
+    tgt = tiny_pair[0]
+    with pytest.raises(card.CardError) as e:
+        tgt.verify(0, -1, [])
+    assert e.value.status == card.CARD_ERANGE
+    with pytest.raises(card.CardError) as e:
+        tgt.verify(0, -1, list(range(33)))
+    assert e.value.status == card.CARD_ERANGE
+    with pytest.raises(card.CardError) as e:
+        tgt.verify(tgt.cfg.max_ctx - 2, -1, [1, 2, 3])
+    assert e.value.status == card.CARD_ECAPACITY
+    kv = tgt.kv(-1)
+    st = card.card_verify(tgt.cfg, None, kv, 0, tgt.cand, 1, tgt.workspace, None, tgt.out, None)
+    assert st == card.CARD_EINVAL
