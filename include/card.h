@@ -144,6 +144,17 @@ int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weigh
                              card_verify_result* out_dev, int32_t* row_argmax_dev,
                              float* logits_dev);
 
+/* Measurement hook (benchmark only).  While enabled, card_verify brackets every launch of one
+ * kernel kind with a pair of HIP events recorded on the call's stream, up to max_launches
+ * pairs; card_profile_collect waits for them, writes each launch's duration in milliseconds
+ * to ms_host (host array of max_launches floats), returns the count in *n_host and disables
+ * the hook.  Not thread-safe; creates HIP events, allocates no device memory. */
+typedef enum card_kernel_kind {
+    CARD_K_QKV = 0, CARD_K_ATTN = 1, CARD_K_WO = 2, CARD_K_GATE_UP = 3, CARD_K_DOWN = 4, CARD_K_LM_HEAD = 5
+} card_kernel_kind;
+int card_profile_enable(int32_t kind, int32_t max_launches);
+int card_profile_collect(float* ms_host, int32_t* n_host);
+
 /* Test helper: copies K (rotated) and V of positions [first_slot, first_slot+count) of one
  * layer out of the paged cache into plain fp32 arrays [count][n_kv_heads][head_dim] (dev). */
 int card_kv_gather(const card_model_cfg* cfg, const card_kv* kv, int32_t layer,

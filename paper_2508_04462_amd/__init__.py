@@ -27,6 +27,9 @@ from .binding import (  # noqa: F401
     card_verify,
     card_verify_debug_logits,
     card_kv_gather,
+    card_profile_enable,
+    card_profile_collect,
+    KERNEL_KINDS,
     card_cache_create,
     card_cache_destroy,
     card_cache_write,

@@ -76,6 +76,10 @@ lib.card_verify_debug_logits.restype = C.c_int
 lib.card_verify_debug_logits.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P, _P]
 lib.card_kv_gather.restype = C.c_int
 lib.card_kv_gather.argtypes = [_cfgp, _kvp, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P]
+lib.card_profile_enable.restype = C.c_int
+lib.card_profile_enable.argtypes = [C.c_int32, C.c_int32]
+lib.card_profile_collect.restype = C.c_int
+lib.card_profile_collect.argtypes = [_f32p, _i32p]
 lib.card_cache_create.restype = C.c_int
 lib.card_cache_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(_P)]
 lib.card_cache_destroy.restype = None
@@ -140,6 +144,21 @@ def card_kv_gather(cfg, kv: CardKV, layer: int, first_slot: int, count: int, k_o
                    stream=None) -> int:
     return lib.card_kv_gather(C.byref(cfg), C.byref(kv), layer, first_slot, count, _ptr(k_out_dev),
                               _ptr(v_out_dev), _ptr(stream))
+
+
+KERNEL_KINDS = {"qkv": 0, "attn": 1, "wo": 2, "gate_up": 3, "down": 4, "lm_head": 5}
+
+
+def card_profile_enable(kind: int, max_launches: int) -> int:
+    return lib.card_profile_enable(kind, max_launches)
+
+
+def card_profile_collect(max_launches: int):
+    """Returns (status, [ms per launch])."""
+    buf = (C.c_float * max_launches)()
+    n = C.c_int32(0)
+    st = lib.card_profile_collect(buf, C.byref(n))
+    return st, list(buf[: n.value])
 
 
 def _i32(seq):

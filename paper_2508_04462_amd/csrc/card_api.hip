@@ -1,6 +1,8 @@
 // C ABI of libcard: argument checks and the launch sequence of one verification step.
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include "card.h"
 #include "card_kernels.hip"
 
@@ -11,6 +13,28 @@ namespace {
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? CARD_OK : CARD_EDEVICE; }
+
+// benchmark hook: event pairs around one kernel kind
+struct Profile {
+    int kind = -1;
+    int used = 0;
+    std::vector<hipEvent_t> start, stop;
+};
+Profile g_prof;
+
+struct ProfScope {
+    hipStream_t st;
+    int idx = -1;
+    ProfScope(int kind, hipStream_t s) : st(s) {
+        if (g_prof.kind == kind && g_prof.used < int(g_prof.start.size())) {
+            idx = g_prof.used++;
+            (void)hipEventRecord(g_prof.start[idx], st);
+        }
+    }
+    ~ProfScope() {
+        if (idx >= 0) (void)hipEventRecord(g_prof.stop[idx], st);
+    }
+};
 
 template <int MT>
 int launch_gemm(int epi, const GemmArgs& a, const GemmPlan& p, hipStream_t st) {
@@ -126,6 +150,7 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
             a.q_dim = qd;
             a.kv_dim = kvd;
             a.n_kv_heads = cfg->n_kv_heads;
+            ProfScope ps(CARD_K_QKV, st);
             if (gemm(EPI_QKV, r, a, L.p_qkv, st) != CARD_OK) return CARD_EDEVICE;
         }
         {
@@ -147,6 +172,7 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
             a.part = reinterpret_cast<float*>(ws + L.apart_off);
             a.counters = acnt;
             a.att = att;
+            ProfScope ps(CARD_K_ATTN, st);
             const dim3 grid(cfg->n_kv_heads * row_pairs * a_splits), block(kAttnWaves * 64);
             if (h == 128)
                 hipLaunchKernelGGL(k_attn<128>, grid, block, 0, st, a);
@@ -158,6 +184,7 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
             GemmArgs a = base_args(lb, L.wo, L.p_wo, att, qd, r, ws, L);
             a.x = x;
             a.ss_out = ss;
+            ProfScope ps(CARD_K_WO, st);
             if (gemm(EPI_RESID, r, a, L.p_wo, st) != CARD_OK) return CARD_EDEVICE;
         }
         {
@@ -169,12 +196,14 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
             a.eps = cfg->rms_eps;
             a.act = act;
             a.F = cfg->d_ffn;
+            ProfScope ps(CARD_K_GATE_UP, st);
             if (gemm(EPI_SWIGLU, r, a, L.p_gu, st) != CARD_OK) return CARD_EDEVICE;
         }
         {
             GemmArgs a = base_args(lb, L.wd, L.p_wd, act, cfg->d_ffn, r, ws, L);
             a.x = x;
             a.ss_out = ss;
+            ProfScope ps(CARD_K_DOWN, st);
             if (gemm(EPI_RESID, r, a, L.p_wd, st) != CARD_OK) return CARD_EDEVICE;
         }
     }
@@ -187,6 +216,7 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
         a.eps = cfg->rms_eps;
         a.best = reinterpret_cast<unsigned long long*>(ws + L.best_off);
         a.logits = logits;
+        ProfScope ps(CARD_K_LM_HEAD, st);
         if (gemm(EPI_LMHEAD, r, a, L.p_lm, st) != CARD_OK) return CARD_EDEVICE;
     }
     {
@@ -301,6 +331,32 @@ int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weigh
     if (!logits_dev) return CARD_EINVAL;
     return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, workspace_dev, stream, out_dev,
                        row_argmax_dev, logits_dev);
+}
+
+int card_profile_enable(int32_t kind, int32_t max_launches) {
+    if (kind < CARD_K_QKV || kind > CARD_K_LM_HEAD || max_launches <= 0) return CARD_EINVAL;
+    while (int(g_prof.start.size()) < max_launches) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return CARD_EDEVICE;
+        g_prof.start.push_back(a);
+        g_prof.stop.push_back(b);
+    }
+    g_prof.kind = kind;
+    g_prof.used = 0;
+    return CARD_OK;
+}
+
+int card_profile_collect(float* ms_host, int32_t* n_host) {
+    if (!ms_host || !n_host) return CARD_EINVAL;
+    const int n = g_prof.used;
+    g_prof.kind = -1;
+    g_prof.used = 0;
+    for (int i = 0; i < n; ++i) {
+        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) return CARD_EDEVICE;
+        if (hipEventElapsedTime(&ms_host[i], g_prof.start[i], g_prof.stop[i]) != hipSuccess) return CARD_EDEVICE;
+    }
+    *n_host = n;
+    return CARD_OK;
 }
 
 int card_kv_gather(const card_model_cfg* cfg, const card_kv* kv, int32_t layer, int32_t first_slot, int32_t count,

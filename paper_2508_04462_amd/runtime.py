@@ -60,13 +60,16 @@ class Target:
                         self.n_pages, int(pending))
 
     # -- one verification step
-    def enqueue_verify(self, ctx_len: int, pending: int, r: int, logits: Optional[torch.Tensor] = None) -> int:
-        """Enqueue on the current stream using the tokens already in self.cand[:r]; no sync."""
+    def enqueue_verify(self, ctx_len: int, pending: int, r: int, logits: Optional[torch.Tensor] = None,
+                       cand: Optional[torch.Tensor] = None) -> int:
+        """Enqueue on the current stream; candidates come from `cand` (device int32) or from
+        self.cand[:r].  No synchronisation."""
         kv = self.kv(pending)
+        cand = self.cand if cand is None else cand
         if logits is None:
-            return B.card_verify(self.cfg, self.packed, kv, ctx_len, self.cand, r, self.workspace,
+            return B.card_verify(self.cfg, self.packed, kv, ctx_len, cand, r, self.workspace,
                                  self._stream(), self.out, self.row_argmax)
-        return B.card_verify_debug_logits(self.cfg, self.packed, kv, ctx_len, self.cand, r, self.workspace,
+        return B.card_verify_debug_logits(self.cfg, self.packed, kv, ctx_len, cand, r, self.workspace,
                                           self._stream(), self.out, self.row_argmax, logits)
 
     def verify(self, ctx_len: int, pending: int, cand: Sequence[int], want_logits: bool = False) -> Dict:
