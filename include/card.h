@@ -150,7 +150,8 @@ int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weigh
  * to ms_host (host array of max_launches floats), returns the count in *n_host and disables
  * the hook.  Not thread-safe; creates HIP events, allocates no device memory. */
 typedef enum card_kernel_kind {
-    CARD_K_QKV = 0, CARD_K_ATTN = 1, CARD_K_WO = 2, CARD_K_GATE_UP = 3, CARD_K_DOWN = 4, CARD_K_LM_HEAD = 5
+    CARD_K_QKV = 0, CARD_K_ATTN = 1, CARD_K_WO = 2, CARD_K_GATE_UP = 3, CARD_K_DOWN = 4, CARD_K_LM_HEAD = 5,
+    CARD_K_STEP = 6
 } card_kernel_kind;
 int card_profile_enable(int32_t kind, int32_t max_launches);
 int card_profile_collect(float* ms_host, int32_t* n_host);

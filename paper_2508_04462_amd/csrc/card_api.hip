@@ -5,6 +5,7 @@
 
 #include "card.h"
 #include "card_kernels.hip"
+#include "card_mega.hip"
 
 using namespace card;
 
@@ -13,6 +14,10 @@ namespace {
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? CARD_OK : CARD_EDEVICE; }
+
+unsigned long long* g_ts_buf = nullptr;
+int g_ts_layer = 0;
+bool g_use_mega = true;  // TEMPORARY while the persistent kernel is brought up
 
 // benchmark hook: event pairs around one kernel kind
 struct Profile {
@@ -68,6 +73,113 @@ GemmArgs base_args(const char* wbase, const MatDesc& m, const GemmPlan& p, const
     a.part = reinterpret_cast<float*>(ws + L.part_off);
     a.counters = reinterpret_cast<int32_t*>(ws + L.cnt_off);
     return a;
+}
+
+int cu_count() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cus = n;
+    }
+    return cus;
+}
+
+template <int MT, int H>
+int launch_mega(MegaArgs& a, hipStream_t st) {
+    void* params[] = {&a};
+    const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<void*>(k_verify<MT, H>), dim3(a.nwg),
+                                                    dim3(kMegaThreads), params, 0, st);
+    return e == hipSuccess ? CARD_OK : CARD_EDEVICE;
+}
+
+// One persistent cooperative kernel runs the whole step.
+int verify_mega(const card_model_cfg* cfg, const void* packed, const card_kv* kv, int32_t ctx_len,
+                const int32_t* cand, int32_t r, void* workspace, void* stream, card_verify_result* out,
+                int32_t* row_argmax, float* logits) {
+    if (!cfg || !packed || !kv || !cand || !workspace || !out) return CARD_EINVAL;
+    const Layout L = make_layout(cfg);
+    if (!L.ok) return CARD_EINVAL;
+    if (!kv->k_pages || !kv->v_pages || !kv->block_table || kv->n_pages <= 0) return CARD_EINVAL;
+    if (r < 1 || r > cfg->max_r) return CARD_ERANGE;
+    if (ctx_len < 0) return CARD_EINVAL;
+    if (int64_t(ctx_len) + r > cfg->max_ctx) return CARD_ECAPACITY;
+    int cus = cu_count();
+    if (cus <= 0) return CARD_EDEVICE;
+    if (cus > 256) cus = 256;  // the barrier polls at most 256 flag words
+
+    char* ws = static_cast<char*>(workspace);
+    const int h = cfg->head_dim;
+    MegaArgs a = {};
+    a.L = cfg->n_layers;
+    a.d = cfg->d_model;
+    a.qd = cfg->n_q_heads * h;
+    a.kvd = cfg->n_kv_heads * h;
+    a.h = h;
+    a.Hkv = cfg->n_kv_heads;
+    a.G = cfg->n_q_heads / cfg->n_kv_heads;
+    a.F = cfg->d_ffn;
+    a.V = cfg->vocab;
+    a.r = r;
+    a.rp = (r + 7) / 8 * 8;
+    a.ctx_len = ctx_len;
+    a.nwg = cus;
+    a.eps = cfg->rms_eps;
+    a.inv_d = 1.0f / float(cfg->d_model);
+    a.theta = cfg->rope_theta;
+    a.inv_sqrt_h = 1.0f / sqrtf(float(h));
+    a.wbase = static_cast<const char*>(packed);
+    a.embed_off = L.embed_off;
+    a.g_final_off = L.g_final_off;
+    a.layer0_off = L.layer0_off;
+    a.layer_stride = L.layer_stride;
+    a.g_attn_off = L.g_attn_off;
+    a.g_ffn_off = L.g_ffn_off;
+    a.qkv = L.qkv;
+    a.wo = L.wo;
+    a.gu = L.gu;
+    a.wd = L.wd;
+    a.lm = L.lm;
+    a.kpool = static_cast<__bf16*>(kv->k_pages);
+    a.vpool = static_cast<__bf16*>(kv->v_pages);
+    a.pool_layer_elems = size_t(kv->n_pages) * cfg->n_kv_heads * 16 * h;
+    a.block_table = kv->block_table;
+    a.pages_used = ceil_div(ctx_len + r, kKvBlock);
+    a.row_tiles = ceil_div(a.G * r, 16);
+    // cut the context only when a wavefront would walk more than ten pages (pages are pulled into
+    // the near cache ahead of time, so a short walk is cheaper than merging cuts)
+    int splits = ceil_div(a.pages_used, 10 * kMegaWaves);
+    if (splits > L.m_attn_max_splits) splits = L.m_attn_max_splits;
+    a.pages_per_split = ceil_div(a.pages_used, splits);
+    a.a_splits = ceil_div(a.pages_used, a.pages_per_split);
+    a.xres = reinterpret_cast<float*>(ws + L.m_xres_off);
+    a.xfrag = reinterpret_cast<__bf16*>(ws + L.m_xfrag_off);
+    a.ss = reinterpret_cast<float*>(ws + L.m_ss_off);
+    a.qfrag = reinterpret_cast<__bf16*>(ws + L.m_qfrag_off);
+    a.attfrag = reinterpret_cast<__bf16*>(ws + L.m_attfrag_off);
+    a.actfrag = reinterpret_cast<__bf16*>(ws + L.m_actfrag_off);
+    a.apart = reinterpret_cast<float*>(ws + L.m_apart_off);
+    a.xfrag_stride = L.xfrag_stride;
+    a.attfrag_stride = L.attfrag_stride;
+    a.actfrag_stride = L.actfrag_stride;
+    a.qfrag_stride = L.qfrag_stride;
+    a.rope = reinterpret_cast<float*>(ws + L.m_rope_off);
+    a.best = reinterpret_cast<unsigned long long*>(ws + L.m_best_off);
+    a.bar = reinterpret_cast<uint32_t*>(ws + L.m_bar_off);
+    a.acount = reinterpret_cast<uint32_t*>(ws + L.m_acount_off);
+    a.flags = reinterpret_cast<uint32_t*>(ws + L.m_flags_off);
+    a.cand = cand;
+    a.pending = kv->pending_token;
+    a.out = out;
+    a.row_argmax = row_argmax;
+    a.logits = logits;
+    a.ts = g_ts_buf;
+    a.ts_layer = g_ts_layer;
+    hipStream_t st = as_stream(stream);
+    ProfScope ps(CARD_K_STEP, st);
+    if (r <= 16) return h == 128 ? launch_mega<1, 128>(a, st) : launch_mega<1, 64>(a, st);
+    return h == 128 ? launch_mega<2, 128>(a, st) : launch_mega<2, 64>(a, st);
 }
 
 int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv, int32_t ctx_len,
@@ -320,8 +432,8 @@ int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t 
 int card_verify(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv, int32_t ctx_len,
                 const int32_t* cand_tokens_dev, int32_t r, void* workspace_dev, void* stream,
                 card_verify_result* out_dev, int32_t* row_argmax_dev) {
-    return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, workspace_dev, stream, out_dev,
-                       row_argmax_dev, nullptr);
+    return (g_use_mega ? verify_mega : verify_impl)(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r,
+                                                    workspace_dev, stream, out_dev, row_argmax_dev, nullptr);
 }
 
 int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
@@ -329,12 +441,23 @@ int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weigh
                              void* stream, card_verify_result* out_dev, int32_t* row_argmax_dev,
                              float* logits_dev) {
     if (!logits_dev) return CARD_EINVAL;
-    return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, workspace_dev, stream, out_dev,
-                       row_argmax_dev, logits_dev);
+    return (g_use_mega ? verify_mega : verify_impl)(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r,
+                                                    workspace_dev, stream, out_dev, row_argmax_dev, logits_dev);
+}
+
+int card_debug_timeline(void* buf_dev, int32_t layer) {
+    g_ts_buf = static_cast<unsigned long long*>(buf_dev);
+    g_ts_layer = layer;
+    return CARD_OK;
+}
+
+int card_debug_use_mega(int on) {
+    g_use_mega = on != 0;
+    return CARD_OK;
 }
 
 int card_profile_enable(int32_t kind, int32_t max_launches) {
-    if (kind < CARD_K_QKV || kind > CARD_K_LM_HEAD || max_launches <= 0) return CARD_EINVAL;
+    if (kind < CARD_K_QKV || kind > CARD_K_STEP || max_launches <= 0) return CARD_EINVAL;
     while (int(g_prof.start.size()) < max_launches) {
         hipEvent_t a, b;
         if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return CARD_EDEVICE;

@@ -9,6 +9,7 @@
 // fully contiguous 1 KiB load per wavefront and 16x32 tile), keep the r activations in fp32
 // and feed them to the bf16 matrix instruction as a high + low bf16 pair (two instructions per
 // tile; the matrix pipe is ~95 % idle anyway), and accumulate in fp32.
+#pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

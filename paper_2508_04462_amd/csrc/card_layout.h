@@ -43,6 +43,11 @@ struct Layout {
     // workspace (byte offsets)
     size_t x_off, q_off, att_off, act_off, ss_off, part_off, cnt_off, apart_off, acnt_off, best_off,
         rope_off, ws_bytes;
+    // workspace of the persistent kernel (byte offsets) and strides in elements
+    size_t m_xres_off, m_xfrag_off, m_ss_off, m_qfrag_off, m_attfrag_off, m_actfrag_off, m_apart_off, m_bar_off,
+        m_acount_off, m_flags_off, m_best_off, m_rope_off;
+    size_t xfrag_stride, attfrag_stride, actfrag_stride, qfrag_stride;
+    int32_t m_attn_max_splits;
     int32_t ss_groups;   // rows of the sum-of-squares partial table
     int32_t n_counters;  // int32 counters for split-K groups
     int32_t attn_max_splits, attn_row_tiles_max;
@@ -160,6 +165,26 @@ inline Layout make_layout(const card_model_cfg* c) {
     L.acnt_off = take(size_t(c->n_kv_heads) * pairs * 4);
     L.best_off = take(size_t(kMaxR) * 8);
     L.rope_off = take(size_t(kMaxR) * h * 4);  // cos[32][h/2] then sin[32][h/2]
+    // persistent kernel: one copy of every hand-over buffer per layer and phase
+    auto frag_elems = [](int32_t K) { return size_t(ceil_div(K, kTileK)) * 4 * kMaxR * 16; };
+    const int32_t versions = 2 * c->n_layers + 1;
+    L.xfrag_stride = frag_elems(d);
+    L.attfrag_stride = frag_elems(qd);
+    L.actfrag_stride = frag_elems(c->d_ffn);
+    L.qfrag_stride = size_t(c->n_q_heads) * kMaxR * h * 2;
+    L.m_xres_off = take(size_t(versions) * kMaxR * d * 4);
+    L.m_xfrag_off = take(size_t(versions) * L.xfrag_stride * 2);
+    L.m_ss_off = take(size_t(versions) * (d / 16) * kMaxR * 4);
+    L.m_qfrag_off = take(size_t(c->n_layers) * L.qfrag_stride * 2);
+    L.m_attfrag_off = take(size_t(c->n_layers) * L.attfrag_stride * 2);
+    L.m_actfrag_off = take(size_t(c->n_layers) * L.actfrag_stride * 2);
+    L.m_attn_max_splits = 32;
+    L.m_apart_off = take(size_t(c->n_kv_heads) * (2 * G) * L.m_attn_max_splits * 16 * (h + 2) * 4);
+    L.m_bar_off = take(256);
+    L.m_flags_off = take(4 * 1024);
+    L.m_acount_off = take(size_t(c->n_kv_heads) * (2 * G) * 4);
+    L.m_best_off = take(size_t(kMaxR) * 8);
+    L.m_rope_off = take(size_t(kMaxR) * h * 4);
     L.ws_bytes = w;
     L.ok = true;
     return L;

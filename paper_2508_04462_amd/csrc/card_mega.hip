@@ -1,0 +1,1164 @@
+// The whole verification step as ONE persistent kernel (one workgroup per compute unit).
+//
+// Why: at r <= 32 rows a decoder layer is five dependent, HBM-bound phases of 4-30 us each;
+// launched as separate kernels the memory pipe drains at every boundary.  Here the phases are
+// separated by grid barriers instead, and - because weights never depend on activations - every
+// wavefront keeps a 16-fragment (16 KiB) register ring of weight tiles in flight that simply runs
+// ahead across the barrier into the next phase's weights.  HBM keeps streaming while the barrier
+// and the hand-over of the (tiny) activations take place.
+//
+// Hand-over rules (the part has one L2 per compute die, not coherent with the others):
+//   * everything one workgroup writes for another is stored with device scope (write-through);
+//   * every such buffer is written exactly once per call, at an address nobody has read before
+//     in this call (one copy per layer and phase), so plain cached loads can never hit a stale
+//     line; the barrier counter itself is only touched with device-scope atomics.
+//
+// Activations travel between phases already split into bf16 high + low halves and laid out in
+// the operand order of the matrix instruction ("fragment order"): element (row m, column k) of
+// an r x K activation lives at ((k/8) * rp + m) * 16 + k%8 (high half) and +8 (low half), where
+// rp = r rounded up to 8.  A wavefront's operand load for one 32-deep k-step is then one
+// contiguous rp*128-byte run.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "card_kernels.hip"
+#include "card_layout.h"
+
+namespace card {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int uint4v;
+typedef const __attribute__((address_space(1))) void* gptr_t;
+
+constexpr int kMegaWaves = 4;             // one wavefront per SIMD: each may use all 512 vector registers
+constexpr int kMegaThreads = kMegaWaves * 64;
+constexpr int kRing = 32;                 // weight fragments (1 KiB each) in flight per wavefront
+constexpr uint32_t kSpinLimit = 1u << 20; // bounded barrier wait: the kernel always terminates
+
+struct MegaArgs {
+    int32_t L, d, qd, kvd, h, Hkv, G, F, V, r, rp, ctx_len, nwg;
+    float eps, inv_d, theta, inv_sqrt_h;
+    const char* wbase;
+    size_t embed_off, g_final_off, layer0_off, layer_stride, g_attn_off, g_ffn_off;
+    MatDesc qkv, wo, gu, wd, lm;  // lm.off absolute, the others relative to the layer base
+    __bf16* kpool;
+    __bf16* vpool;
+    size_t pool_layer_elems;
+    const int32_t* block_table;
+    int32_t pages_used, a_splits, pages_per_split, row_tiles;
+    // workspace; "v" = residual version: 0 after embed, 2l+1 after O-proj, 2l+2 after down of layer l
+    float* xres;       // [2L+1][32][d]
+    __bf16* xfrag;     // [2L+1][xfrag_stride]
+    float* ss;         // [2L+1][d/16][32]
+    __bf16* qfrag;     // [L][Hkv][G*32][h/8][16]
+    __bf16* attfrag;   // [L][attfrag_stride]
+    __bf16* actfrag;   // [L][actfrag_stride]
+    float* apart;      // [tasks][16*(h+2)], shared by all layers (read back with device-scope loads)
+    size_t xfrag_stride, attfrag_stride, actfrag_stride, qfrag_stride;
+    float* rope;
+    unsigned long long* best;
+    uint32_t* bar;     // [1] exit counter, [2] error flag (zero between calls), [3] barrier epoch
+    uint32_t* flags;   // [nwg] last barrier sequence number each workgroup has reached
+    uint32_t* acount;  // [Hkv * row_tiles] arrival counters of the attention cuts; zero between uses
+    const int32_t* cand;
+    int32_t pending;
+    card_verify_result* out;
+    int32_t* row_argmax;
+    float* logits;
+    unsigned long long* ts;  // optional phase timeline [nwg][32] of layer ts_layer (100 MHz ticks)
+    int32_t ts_layer;
+};
+
+struct __align__(16) MegaSmem {
+    union {
+        float red[kMegaWaves * 8 * 256];              // GEMM: per-wavefront accumulators (after the k-loop)
+        float attn[kMegaWaves * 16 * (128 + 2)];      // attention: per-wavefront (M, L, O)
+    };
+    float tile[2048];        // reduced outputs of one batch: [NB*16 rows][16*MT columns]
+    float row_scale[kMaxR];
+    float wgt[(kMegaWaves + 3) * 16];
+    unsigned long long part_best[512];
+    unsigned long long wg_best[kMaxR];
+    int failed;
+    uint32_t epoch;
+};
+
+// ---- device-scope (write-through) stores -------------------------------------------------
+// 128-bit buffer stores with the device-scope bit: `ubase` is wavefront-uniform, `off` the
+// lane's byte offset from it (< 4 GiB).
+constexpr int kAuxDev = 16;  // sc1: device scope
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ void st_dev_b128(const void* ubase, uint32_t off, uint4v v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, make_rsrc(ubase, 0xffffffffu), int(off), 0, kAuxDev);
+}
+__device__ __forceinline__ void st_dev_f32x8(const float* ubase, uint32_t elem_off, const float (&v)[8]) {
+    st_dev_b128(ubase, elem_off * 4, uint4v{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]),
+                                             __float_as_uint(v[3])});
+    st_dev_b128(ubase, elem_off * 4 + 16, uint4v{__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]),
+                                                  __float_as_uint(v[7])});
+}
+__device__ __forceinline__ void st_dev_bf16(__bf16* p, __bf16 v) {
+    __hip_atomic_store(reinterpret_cast<unsigned short*>(p), __builtin_bit_cast(unsigned short, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t pack_bf16(__bf16 lo16, __bf16 hi16) {
+    return uint32_t(__builtin_bit_cast(unsigned short, lo16)) | (uint32_t(__builtin_bit_cast(unsigned short, hi16)) << 16);
+}
+// eight values -> high and low bf16 halves -> 32 contiguous bytes at element offset `elem_off`
+__device__ __forceinline__ void st_dev_frag8(const __bf16* ubase, size_t elem_off, const float (&v)[8]) {
+    uint4v hi, lo;
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+        __bf16 h0, l0, h1, l1;
+        split_bf16(v[e], h0, l0);
+        split_bf16(v[e + 1], h1, l1);
+        hi[e / 2] = pack_bf16(h0, h1);
+        lo[e / 2] = pack_bf16(l0, l1);
+    }
+    st_dev_b128(ubase, uint32_t(elem_off * 2), hi);
+    st_dev_b128(ubase, uint32_t(elem_off * 2) + 16, lo);
+}
+__device__ __forceinline__ size_t frag_index(int k, int m, int rp) { return (size_t(k >> 3) * rp + m) * 16 + (k & 7); }
+
+// Values derived from the lane index are cheap to recompute but the optimiser likes to hoist
+// them out of the layer loop, where dozens of them then stay live across every phase.  Passing
+// the index through an empty asm at the top of each phase keeps them local to the phase.
+__device__ __forceinline__ int opaque_v(int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+// ---- grid barrier --------------------------------------------------------------------------
+// Stores and loads share one in-order counter on this part.  store_wait<PENDING> returns when
+// all of this thread's stores are acknowledged, given that exactly PENDING loads were issued
+// after the last store (the weight ring's run-ahead) and may stay in flight.
+template <int PENDING>
+__device__ __forceinline__ void store_wait() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    // s_waitcnt vmcnt(PENDING): vmcnt[3:0] | expcnt(7) << 4 | lgkmcnt(15) << 8 | vmcnt[5:4] << 14
+    __builtin_amdgcn_s_waitcnt((PENDING & 15) | (7 << 4) | (15 << 8) | ((PENDING >> 4) << 14));
+}
+
+// Arrive and wait.  A single counter would serialise one device-scope atomic per workgroup
+// (about 10 us for 256 of them under load); instead every workgroup publishes the barrier's
+// sequence number in its own flag word and wavefront 0 of every workgroup polls all flags with
+// one 1 KiB device-scope load.  Sequence numbers keep growing across calls (`epoch`), so flags
+// never need clearing.  Loads complete in issue order per wavefront, so callers keep wavefront
+// 0's queue free of long-latency loads when it gets here.
+__device__ __forceinline__ void grid_wait(const MegaArgs& a, uint32_t& gen, MegaSmem& sm) {
+    __syncthreads();
+    gen += 1;
+    if (threadIdx.x < 64 && !sm.failed) {
+        const uint32_t target = sm.epoch + gen;
+        const int lane = threadIdx.x;
+        if (lane == 0) __hip_atomic_store(&a.flags[blockIdx.x], target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const __amdgpu_buffer_rsrc_t frs = make_rsrc(a.flags, uint32_t(a.nwg) * 4);
+        uint32_t spins = 0;
+        while (true) {
+            const uint4v f = __builtin_amdgcn_raw_buffer_load_b128(frs, lane * 16, 0, kAuxDev);
+            bool ok = true;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (lane * 4 + q < a.nwg) ok = ok && int32_t(f[q] - target) >= 0;
+            if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) break;
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > kSpinLimit) {
+                if (lane == 0) {
+                    sm.failed = 1;
+                    __hip_atomic_store(&a.bar[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                break;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// ---- weight ring ---------------------------------------------------------------------------
+// All streaming loads are buffer loads: a wavefront-uniform 128-bit resource (matrix base and
+// size, in scalar registers), a wavefront-uniform 32-bit byte offset (scalar) and the lane's own
+// 16-byte slot.  No per-lane 64-bit address arithmetic, and reads past the end return zero.
+constexpr int kAuxNT = 2;  // non-temporal: weights are used once
+constexpr int kOutOfRange = int(0x80000000u);  // lane offset beyond any buffer: the load returns 0, touches nothing
+
+// Where the next 16 fragments come from: NBs tiles (stride `tstride`) x 16/NBs k-steps from sbase.
+struct RingSrc {
+    const bf16x8* w;   // matrix base (wavefront-uniform)
+    uint32_t bytes;    // matrix size
+    int32_t Ks, t0, tstride, nvalid, shift, sbase, smax;
+    __device__ __forceinline__ uint32_t off(int idx) const {
+        const int u = idx >> shift;
+        int i = idx & ((1 << shift) - 1);
+        i = i < nvalid ? i : nvalid - 1;
+        int step = sbase + u;
+        step = step < smax ? step : smax;
+        return (uint32_t(t0 + i * tstride) * uint32_t(Ks) + uint32_t(step)) << 10;
+    }
+};
+
+struct PhasePlan {
+    const bf16x8* w;
+    uint32_t bytes;
+    int32_t Ks, Nt, t_first, cnt, s0, s1;  // this workgroup's tiles: t_first + j*nwg, j < cnt; wavefront's k-steps
+};
+
+__device__ __forceinline__ PhasePlan plan_phase(const bf16x8* w, int Nt, int Ks, int wg, int nwg, int rot, int wave) {
+    PhasePlan p;
+    p.w = w;
+    p.bytes = uint32_t(Nt) * uint32_t(Ks) * 1024u;
+    p.Ks = Ks;
+    p.Nt = Nt;
+    p.t_first = (wg + rot) % nwg;
+    p.cnt = p.t_first < Nt ? (Nt - p.t_first + nwg - 1) / nwg : 0;
+    p.s0 = (wave * Ks) / kMegaWaves;
+    p.s1 = ((wave + 1) * Ks) / kMegaWaves;
+    return p;
+}
+
+template <int NB>
+__device__ __forceinline__ RingSrc first_src(const PhasePlan& p, int nwg) {
+    RingSrc s;
+    s.w = p.w;
+    s.bytes = p.bytes;
+    s.Ks = p.Ks;
+    s.t0 = p.cnt > 0 ? p.t_first : 0;
+    s.tstride = p.cnt > 0 ? nwg : 0;
+    s.nvalid = p.cnt > 0 ? (p.cnt < NB ? p.cnt : NB) : 1;
+    s.shift = NB == 1 ? 0 : NB == 2 ? 1 : NB == 4 ? 2 : 3;
+    s.sbase = p.s0;
+    // steps past the wavefront's share re-read its last fragment (a cache hit), never new bytes
+    s.smax = p.s1 > p.s0 ? p.s1 - 1 : (p.s0 < p.Ks ? p.s0 : p.Ks - 1);
+    return s;
+}
+
+__device__ __forceinline__ bf16x8 ring_load(__amdgpu_buffer_rsrc_t rs, int lane16, uint32_t off) {
+    return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs, lane16, int(off), kAuxNT));
+}
+
+__device__ __forceinline__ void ring_fill(bf16x8 (&ring)[kRing], const RingSrc& s, int lane) {
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(s.w, s.bytes);
+#pragma unroll
+    for (int idx = 0; idx < kRing; ++idx) ring[idx] = ring_load(rs, lane * 16, s.off(idx));
+}
+
+template <int HALF>
+__device__ __forceinline__ void ring_fill_half(bf16x8 (&ring)[kRing], const RingSrc& s, int lane) {
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(s.w, s.bytes);
+#pragma unroll
+    for (int idx = HALF * (kRing / 2); idx < (HALF + 1) * (kRing / 2); ++idx)
+        ring[idx] = ring_load(rs, lane * 16, s.off(idx));
+}
+
+// B operand (activations) of one k-step: high and low halves for MT row tiles.  `xoff` is the
+// lane's byte offset inside a k-step's block ((kc * rp + row) * 32, or -1 for rows >= r).
+template <int MT>
+__device__ __forceinline__ void load_x(__amdgpu_buffer_rsrc_t xr, const int (&xoff)[MT], int step, int s1, int rp,
+                                       bf16x8 (&xh)[MT], bf16x8 (&xl)[MT]) {
+    const uint32_t soff = uint32_t(step) * uint32_t(rp) * 128u;
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+        uint4v hi = {0u, 0u, 0u, 0u}, lo = {0u, 0u, 0u, 0u};
+        if (xoff[j] >= 0 && step < s1) {
+            hi = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[j], int(soff), 0);
+            lo = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[j] + 16, int(soff), 0);
+        }
+        xh[j] = __builtin_bit_cast(bf16x8, hi);
+        xl[j] = __builtin_bit_cast(bf16x8, lo);
+    }
+}
+
+enum MegaEpi { ME_QKV = 0, ME_RESID = 1, ME_SWIGLU = 2, ME_LM = 3 };
+
+struct EpiArgs {
+    int32_t layer;
+    const float* ss_in;      // [d/16][32] partial sums of squares of the input rows (norm phases)
+    // RESID
+    const float* xres_old;
+    float* xres_new;
+    __bf16* xfrag_new;
+    float* ss_new;
+    const float* gain_next;
+    // QKV
+    __bf16* qfrag;
+    __bf16* kpool;
+    __bf16* vpool;
+    // SWIGLU
+    __bf16* actfrag;
+};
+
+// ---- one weight-streaming GEMM phase ----------------------------------------------------------
+// out[m][n] = sum_k x[m][k] W[n][k] for this workgroup's n-tiles; the eight wavefronts cut K.
+// RUN_AHEAD = false: the ring is left empty at the end (the caller refills it later); used before
+// the attention phase, which needs the registers.
+template <int NB, int MT, int EPI, bool RUN_AHEAD = true>
+__device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P, const __bf16* xf, uint32_t xf_bytes,
+                                           const EpiArgs& ea, bf16x8 (&ring)[kRing], const RingSrc& next_first,
+                                           MegaSmem& sm, int wave, int lane) {
+    constexpr int U = kRing / NB;  // k-steps per ring cycle
+    // activation ring: depth in k-steps (one ring cycle, halved where two row tiles would not fit)
+    constexpr int XD = NB == 1 ? (MT == 2 ? 4 : 8) : U;
+    constexpr int COLS = 16 * MT;
+    const int tid = opaque_v(threadIdx.x);
+    lane = tid & 63;
+    const int r = a.r, rp = a.rp;
+
+    // Loads whose results are only needed after the k-loop are issued first: the per-tile sums of
+    // squares behind the RMSNorm scale (SSL lanes per row, SSQ values each) ...
+    constexpr int SSL = kMegaThreads / kMaxR, SSQ = 256 / SSL;
+    float ssv[SSQ];
+    const int ss_row = tid / SSL, ss_sub = tid % SSL, n_part = a.d >> 4;
+    if constexpr (EPI != ME_RESID) {
+#pragma unroll
+        for (int q = 0; q < SSQ; ++q) {
+            const int g = ss_sub + SSL * q;
+            ssv[q] = (ss_row < r && g < n_part) ? ea.ss_in[g * kMaxR + ss_row] : 0.f;
+        }
+    }
+    // ... and the old residual values and next gains of the tile this thread will finish
+    float xo8[8], gn8[8];
+    if constexpr (EPI == ME_RESID) {
+        const int c = tid & 1, m = (tid >> 1) % kMaxR, i = tid / (2 * kMaxR);
+        const bool on = i < min(NB, P.cnt) && m < r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xo8[e] = gn8[e] = 0.f;
+        if (on) {
+            const int n0 = (P.t_first + i * a.nwg) * 16 + c * 8;
+            const float4 x0 = *reinterpret_cast<const float4*>(ea.xres_old + size_t(m) * a.d + n0);
+            const float4 x1 = *reinterpret_cast<const float4*>(ea.xres_old + size_t(m) * a.d + n0 + 4);
+            const float4 g0 = *reinterpret_cast<const float4*>(ea.gain_next + n0);
+            const float4 g1 = *reinterpret_cast<const float4*>(ea.gain_next + n0 + 4);
+            xo8[0] = x0.x; xo8[1] = x0.y; xo8[2] = x0.z; xo8[3] = x0.w;
+            xo8[4] = x1.x; xo8[5] = x1.y; xo8[6] = x1.z; xo8[7] = x1.w;
+            gn8[0] = g0.x; gn8[1] = g0.y; gn8[2] = g0.z; gn8[3] = g0.w;
+            gn8[4] = g1.x; gn8[5] = g1.y; gn8[6] = g1.z; gn8[7] = g1.w;
+        }
+    }
+
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(xf, xf_bytes);
+    int xoff[MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+        const int row = j * 16 + (lane & 15);
+        xoff[j] = row < r ? ((lane >> 4) * rp + row) * 32 : kOutOfRange;
+    }
+    const int n_batches = (P.cnt + NB - 1) / NB;
+    const int n_steps = P.s1 - P.s0;
+    const int n_chunks = (n_steps + U - 1) / U;
+    const int vtot = n_chunks * U;  // virtual k-steps of one batch (the tail beyond s1 reads zeros)
+    RingSrc src = first_src<NB>(P, a.nwg);
+
+    // The activations (B operand) sit in a second register ring, XD k-steps deep, refilled slot
+    // by slot right after use, exactly like the weight ring.  Loads complete in issue order, so
+    // waiting for the operand of step s only forces loads issued before step s - XD: a full ring
+    // cycle of weight loads stays in flight.  The ring wraps at the end of a batch (every batch
+    // uses the same activations).
+    bf16x8 xh[XD][MT], xl[XD][MT];
+    auto load_x = [&](int v, bf16x8 (&h)[MT], bf16x8 (&l)[MT]) {
+        const int step = P.s0 + v;
+        const uint32_t soff = uint32_t(step) * uint32_t(rp) * 128u;
+#pragma unroll
+        for (int j = 0; j < MT; ++j) {
+            // no branch: an offset past the end of the buffer makes the load return zeros
+            const int vo = step < P.s1 ? xoff[j] : kOutOfRange;
+            h[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, vo, int(soff), 0));
+            l[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, vo + 16, int(soff), 0));
+        }
+    };
+    if (n_batches > 0 && n_chunks > 0) {
+#pragma unroll
+        for (int u = 0; u < XD; ++u) load_x(u, xh[u], xl[u]);
+    }
+
+    for (int b = 0; b < n_batches; ++b) {
+        floatx4 acc[NB][MT];
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j < MT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const int nvalid = min(NB, P.cnt - b * NB);
+
+        for (int c = 0; c < n_chunks; ++c) {
+            // source of the refill: next ring cycle of this batch, else next batch, else next phase
+            RingSrc nsrc = src;
+            bool run_ahead = false;  // last ring cycle of the phase: only half the ring runs ahead now
+            if (c + 1 < n_chunks) {
+                nsrc.sbase = src.sbase + U;
+            } else if (b + 1 < n_batches) {
+                nsrc.sbase = P.s0;
+                nsrc.t0 = src.t0 + NB * a.nwg;
+                nsrc.nvalid = min(NB, P.cnt - (b + 1) * NB);
+            } else {
+                nsrc = next_first;
+                run_ahead = true;
+            }
+            const __amdgpu_buffer_rsrc_t nrs = make_rsrc(nsrc.w, nsrc.bytes);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                constexpr int dummy = 0;
+                (void)dummy;
+                const int slot = u % XD;
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    const int idx = u * NB + i;
+#pragma unroll
+                    for (int j = 0; j < MT; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[idx], xh[slot][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[idx], xl[slot][j], acc[i][j], 0, 0, 0);
+                    }
+                    // the part of the ring that must not run ahead yet loads "nothing" (no branch)
+                    const bool hold = run_ahead && !(RUN_AHEAD && idx < kRing / 2);
+                    ring[idx] = ring_load(nrs, hold ? kOutOfRange : lane * 16, nsrc.off(idx));
+                }
+                int vn = c * U + u + XD;
+                const bool wraps = vn >= vtot;
+                vn = wraps ? vn - vtot : vn;
+                load_x(vn, xh[slot], xl[slot]);
+            }
+            src = nsrc;
+        }
+        if (n_chunks == 0 && b + 1 == n_batches) {
+            // a wavefront without k-steps (K shorter than 8 steps) still moves the first half on
+            if (RUN_AHEAD) ring_fill_half<0>(ring, next_first, lane);
+        }
+        if constexpr (EPI != ME_RESID) {
+            if (b == 0) {
+                float sq = 0.f;
+#pragma unroll
+                for (int q = 0; q < SSQ; ++q) sq += ssv[q];
+                if (n_part > 256 && ss_row < r)
+                    for (int g = ss_sub + 256; g < n_part; g += SSL) sq += ea.ss_in[g * kMaxR + ss_row];
+#pragma unroll
+                for (int o = 1; o < SSL; o <<= 1) sq += __shfl_xor(sq, o);
+                if (ss_sub == 0 && ss_row < r) sm.row_scale[ss_row] = 1.0f / sqrtf(sq * a.inv_d + a.eps);
+            }
+        }
+
+        // ---- reduce the eight wavefronts (fixed order) --------------------------------------
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j < MT; ++j)
+                *reinterpret_cast<floatx4*>(&sm.red[(wave * NB * MT + i * MT + j) * 256 + lane * 4]) = acc[i][j];
+        __syncthreads();
+        for (int e = tid; e < NB * MT * 256; e += kMegaThreads) {
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < kMegaWaves; ++w) s += sm.red[w * NB * MT * 256 + e];
+            const int t = e >> 8, l = (e & 255) >> 2, v = e & 3;
+            const int i = t / MT, j = t % MT;
+            sm.tile[(i * 16 + (l >> 4) * 4 + v) * COLS + j * 16 + (l & 15)] = s;
+        }
+        __syncthreads();
+
+        // ---- epilogue ----------------------------------------------------------------------------
+        const int tile0 = P.t_first + b * NB * a.nwg;  // tile i of the batch: tile0 + i * nwg
+        if constexpr (EPI == ME_RESID) {
+            // work item: (tile i, row m, half c of the 16 columns); lanes 2q and 2q+1 share a row
+            const int c = tid & 1, m = (tid >> 1) % kMaxR, i = tid / (2 * kMaxR);
+            const bool on = i < nvalid && m < r;
+            float ssum = 0.f;
+            if (on) {
+                const int n0 = (tile0 + i * a.nwg) * 16 + c * 8;
+                if (b > 0) {  // later batches were not pre-loaded
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        xo8[e] = ea.xres_old[size_t(m) * a.d + n0 + e];
+                        gn8[e] = ea.gain_next[n0 + e];
+                    }
+                }
+                float nv[8], gv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    nv[e] = xo8[e] + sm.tile[(i * 16 + c * 8 + e) * COLS + m];
+                    ssum += nv[e] * nv[e];
+                    gv[e] = nv[e] * gn8[e];
+                }
+                st_dev_f32x8(ea.xres_new, uint32_t(m) * a.d + n0, nv);
+                st_dev_frag8(ea.xfrag_new, frag_index(n0, m, rp), gv);
+            }
+            ssum += __shfl_xor(ssum, 1);
+            if (on && c == 0) st_agent(ea.ss_new + size_t(tile0 + i * a.nwg) * kMaxR + m, ssum);
+            static_assert(NB * 2 * kMaxR <= kMegaThreads, "one pass");
+        } else if constexpr (EPI == ME_SWIGLU) {
+            const int m = tid % kMaxR, i = tid / kMaxR;
+            if (i < nvalid && m < r) {
+                const float sc = sm.row_scale[m];
+                float av[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float g = sm.tile[(i * 16 + e) * COLS + m] * sc;
+                    const float u = sm.tile[(i * 16 + 8 + e) * COLS + m] * sc;
+                    av[e] = g / (1.f + expf(-g)) * u;
+                }
+                const int f0 = (tile0 + i * a.nwg) * 8;
+                st_dev_frag8(ea.actfrag, frag_index(f0, m, rp), av);
+            }
+        } else if constexpr (EPI == ME_LM) {
+            if (a.logits) {
+                for (int e = tid; e < NB * 16 * r; e += kMegaThreads) {
+                    const int nl = e % (NB * 16), m = e / (NB * 16);
+                    const int i = nl >> 4;
+                    const int n = (tile0 + i * a.nwg) * 16 + (nl & 15);
+                    if (i < nvalid && n < a.V) a.logits[size_t(m) * a.V + n] = sm.tile[nl * COLS + m] * sm.row_scale[m];
+                }
+            }
+            constexpr int PARTS = kMegaThreads / COLS;
+            constexpr int ROWS_PER = NB * 16 / PARTS;
+            static_assert(ROWS_PER >= 1, "rows per thread");
+            {
+                const int m = tid % COLS, part = tid / COLS;
+                unsigned long long best = 0ull;
+                if (m < r) {
+                    const float sc = sm.row_scale[m];
+#pragma unroll
+                    for (int q = 0; q < ROWS_PER; ++q) {
+                        const int nl = part * ROWS_PER + q, i = nl >> 4;
+                        const int n = (tile0 + i * a.nwg) * 16 + (nl & 15);
+                        if (i < nvalid && n < a.V) {
+                            const unsigned long long key =
+                                (static_cast<unsigned long long>(float_key(sm.tile[nl * COLS + m] * sc)) << 32) |
+                                (0xffffffffu - uint32_t(n));
+                            best = key > best ? key : best;
+                        }
+                    }
+                }
+                sm.part_best[part * COLS + m] = best;
+            }
+            __syncthreads();
+            if (tid < r) {
+                unsigned long long best = sm.wg_best[tid];
+                for (int part = 0; part < PARTS; ++part) {
+                    const unsigned long long k = sm.part_best[part * COLS + tid];
+                    best = k > best ? k : best;
+                }
+                sm.wg_best[tid] = best;
+            }
+        } else {  // ME_QKV
+            // packed rows: [q heads | k heads | v heads]; in q and k heads row 2p is element p of the
+            // head and row 2p+1 its rotation partner p + h/2.  Work item: (tile, row m, which half).
+            const int which = tid & 1, m = (tid >> 1) % kMaxR, i = tid / (2 * kMaxR);
+            if (i < nvalid && m < r) {
+                const int h = a.h, half = h >> 1;
+                const int prow = (tile0 + i * a.nwg) * 16;
+                const float sc = sm.row_scale[m];
+                const int slot = a.ctx_len + m;
+                const int page = a.block_table[slot >> 4], tk = slot & 15;
+                if (prow < a.qd + a.kvd) {
+                    const bool is_q = prow < a.qd;
+                    const int rel = is_q ? prow : prow - a.qd;
+                    const int head = rel / h, p0 = (rel % h) >> 1;  // eight pairs p0 .. p0+7 (p0 % 8 == 0)
+                    float ov[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float z0 = sm.tile[(i * 16 + 2 * e) * COLS + m] * sc;
+                        const float z1 = sm.tile[(i * 16 + 2 * e + 1) * COLS + m] * sc;
+                        const float cs = a.rope[m * half + p0 + e], sn = a.rope[kMaxR * half + m * half + p0 + e];
+                        ov[e] = which == 0 ? z0 * cs - z1 * sn : z1 * cs + z0 * sn;
+                    }
+                    const int j0 = p0 + which * half;  // first of eight consecutive head elements
+                    if (is_q) {
+                        const int kvh = head / a.G, gl = head % a.G;
+                        const int rho = m * a.G + gl;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) ov[e] *= a.inv_sqrt_h;
+                        st_dev_frag8(ea.qfrag, ((size_t(kvh) * (a.G * kMaxR) + rho) * (h >> 3) + (j0 >> 3)) * 16, ov);
+                    } else {
+                        const size_t ko = (size_t(page) * a.Hkv + head) * (16 * h) + ((j0 >> 3) * 16 + tk) * 8;
+                        uint4v w;
+#pragma unroll
+                        for (int e = 0; e < 8; e += 2)
+                            w[e / 2] = pack_bf16(static_cast<__bf16>(ov[e]), static_cast<__bf16>(ov[e + 1]));
+                        st_dev_b128(ea.kpool, uint32_t(ko * 2), w);
+                    }
+                }
+            }
+            // V rows: work item (tile, head element j of the tile); the r tokens of one element are
+            // consecutive 2-byte slots inside a page row, written as the widest aligned stores
+            const int jj = (tid & 1) * 8 + ((tid >> 1) & 7);
+            const bool v_lane = ((tid >> 1) % kMaxR) < 8;
+            if (i < nvalid && v_lane && (tile0 + i * a.nwg) * 16 >= a.qd + a.kvd) {
+                const int h = a.h;
+                const int rel = (tile0 + i * a.nwg) * 16 - a.qd - a.kvd + jj;
+                const int head = rel / h, jg = rel % h;
+                int m2 = 0;
+                while (m2 < r) {
+                    const int slot = a.ctx_len + m2;
+                    const int page = a.block_table[slot >> 4], tk = slot & 15;
+                    const int run = min(r - m2, 16 - tk);
+                    const size_t vo = (size_t(page) * a.Hkv + head) * (16 * h) + jg * 16 + tk;
+                    int q = 0;
+                    while (q < run) {
+                        auto val = [&](int t) {
+                            return static_cast<__bf16>(sm.tile[(i * 16 + jj) * COLS + m2 + t] * sm.row_scale[m2 + t]);
+                        };
+                        if (((tk + q) & 7) == 0 && q + 8 <= run) {
+                            uint4v w;
+#pragma unroll
+                            for (int e = 0; e < 8; e += 2) w[e / 2] = pack_bf16(val(q + e), val(q + e + 1));
+                            st_dev_b128(ea.vpool, uint32_t((vo + q) * 2), w);
+                            q += 8;
+                        } else if (((tk + q) & 1) == 0 && q + 2 <= run) {
+                            __hip_atomic_store(reinterpret_cast<uint32_t*>(ea.vpool + vo + q), pack_bf16(val(q), val(q + 1)),
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            q += 2;
+                        } else {
+                            st_dev_bf16(ea.vpool + vo + q, val(q));
+                            q += 1;
+                        }
+                    }
+                    m2 += run;
+                }
+            }
+        }
+        __syncthreads();  // red / tile are reused by the next batch
+    }
+    if (RUN_AHEAD) {
+        if (n_batches == 0) ring_fill_half<0>(ring, next_first, lane);  // no tile here: just move the ring on
+        // second half of the run-ahead: issued after this phase's stores, so that the barrier's wait
+        // for those stores (in-order counter) leaves exactly these kRing/2 loads in flight
+        // (the wavefront that polls the barrier issues its half after the barrier instead)
+        if (wave != 0) ring_fill_half<1>(ring, next_first, lane);
+    }
+}
+
+// ---- chain attention phase ------------------------------------------------------------------------
+// Rows = the G query heads sharing one KV head x the r candidates; row (m, g) sees keys at
+// positions <= ctx_len + m (the target verifies a plain chain, never a tree: Cache Correction,
+// last paragraph).  Task = (kv head, 16-row tile, cut of the page list); the eight wavefronts of
+// a workgroup take pages round-robin.  Per 16-token page: S^T = K Q^T on the matrix pipe (K page
+// stored in operand order), online softmax per row with wavefront-level reductions,
+// O^T += V^T P^T with the probability tile fed straight from the accumulator registers.
+// Wavefront partials (max, sum, O) meet in LDS; cuts meet in global partials merged by whichever
+// workgroup arrives last.  Pages that hold only old context do not depend on this step's QKV
+// phase, so their loads are issued BEFORE the grid barrier that precedes attention.
+struct AttnTask {
+    int kvh, rt, split, pg0, pg1;
+};
+
+__device__ __forceinline__ AttnTask attn_task(const MegaArgs& a, int task) {
+    AttnTask t;
+    t.split = task % a.a_splits;
+    t.rt = (task / a.a_splits) % a.row_tiles;
+    t.kvh = task / (a.a_splits * a.row_tiles);
+    t.pg0 = t.split * a.pages_per_split;
+    t.pg1 = min(a.pages_used, t.pg0 + a.pages_per_split);
+    return t;
+}
+
+template <int H>
+__device__ __forceinline__ void attn_load_page(const MegaArgs& a, const __bf16* kpool, const __bf16* vpool, int kvh,
+                                               int pg, int lane, bf16x8 (&kf)[H / 32], short4v (&vf)[H / 16]) {
+    const int col = lane & 15, kq = lane >> 4;
+    const int pid = a.block_table[pg];
+    const size_t base = (size_t(pid) * a.Hkv + kvh) * (16 * H);
+    const bf16x8* kp = reinterpret_cast<const bf16x8*>(kpool + base) + lane;
+    const short4v* vp = reinterpret_cast<const short4v*>(vpool + base) + (col * 4 + kq);
+#pragma unroll
+    for (int st = 0; st < H / 32; ++st) kf[st] = kp[st * 64];
+#pragma unroll
+    for (int i = 0; i < H / 16; ++i) vf[i] = vp[i * 64];
+}
+
+// Second half of an attention task, kept out of line so that its index arithmetic does not
+// compete for registers with the page loop: merge the eight wavefront partials in LDS, then
+// either finish (context not cut) or hand the cut's partial over and let the last workgroup of
+// this (kv head, row tile) merge all cuts.
+template <int H>
+__device__ __attribute__((noinline)) void attn_finish(MegaSmem& sm, float* apart, uint32_t* acount, __bf16* attfrag_l,
+                                                      int G, int rp, int R, int a_splits, int row_tiles, int task,
+                                                      int split, int kvh, int rt) {
+    constexpr int PART = 16 * (H + 2);
+    const int tid = threadIdx.x;
+        if (tid < 16) {
+            float mg = -1e30f;
+            for (int w = 0; w < kMegaWaves; ++w) mg = fmaxf(mg, sm.attn[w * PART + tid]);
+            float l = 0.f;
+            for (int w = 0; w < kMegaWaves; ++w) {
+                const float f = expf(sm.attn[w * PART + tid] - mg);
+                sm.wgt[w * 16 + tid] = f;
+                l += f * sm.attn[w * PART + 16 + tid];
+            }
+            sm.wgt[kMegaWaves * 16 + tid] = mg;
+            sm.wgt[(kMegaWaves + 1) * 16 + tid] = l;
+        }
+        __syncthreads();
+        // work item: (row, chunk of 8 head elements); H/8 * 16 <= 256 items
+        const int row = tid / (H / 8), ch = tid % (H / 8);
+        const bool item = tid < 16 * (H / 8);
+        const int rr = rt * 16 + row;
+        float v8[8];
+        if (item) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                float acc = 0.f;
+                for (int w = 0; w < kMegaWaves; ++w) acc += sm.wgt[w * 16 + row] * sm.attn[w * PART + 32 + row * H + ch * 8 + q];
+                v8[q] = acc;
+            }
+        }
+        float* att_part = apart + size_t(task) * PART;
+        bool finish = a_splits == 1;
+        float inv_l = 0.f;
+        if (a_splits == 1) {
+            if (item) inv_l = 1.0f / sm.wgt[(kMegaWaves + 1) * 16 + row];
+        } else {
+            // hand the cut's partial over; the last workgroup of this (kv head, row tile) merges
+            if (item) st_dev_f32x8(att_part, 32 + row * H + ch * 8, v8);
+            if (tid < 16) {
+                st_agent(att_part + tid, sm.wgt[kMegaWaves * 16 + tid]);
+                st_agent(att_part + 16 + tid, sm.wgt[(kMegaWaves + 1) * 16 + tid]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            int* flag = reinterpret_cast<int*>(&sm.wgt[(kMegaWaves + 2) * 16]);
+            if (tid == 0) {
+                const uint32_t prev = __hip_atomic_fetch_add(&acount[kvh * row_tiles + rt], 1u, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT);
+                *flag = prev == uint32_t(a_splits) - 1;
+            }
+            __syncthreads();
+            finish = *flag != 0;
+            if (finish) {
+                const int S = a_splits;
+                const float* base = apart + size_t(task - split) * PART;
+                const __amdgpu_buffer_rsrc_t prs = make_rsrc(base, uint32_t(S) * PART * 4);
+                float* wl = sm.attn;  // [S][16] weights then [16] totals (S <= 32)
+                // all (cut, row) maxima and sums in one round of device-scope loads (S <= 32)
+                float* ml = sm.attn + 1024;  // [S][16] maxima then [S][16] sums
+                for (int e = tid; e < S * 16; e += kMegaThreads) {
+                    const int sp = e >> 4, rw = e & 15;
+                    ml[e] = ld_agent(base + size_t(sp) * PART + rw);
+                    ml[512 + e] = ld_agent(base + size_t(sp) * PART + 16 + rw);
+                }
+                __syncthreads();
+                if (tid < 16) {
+                    float mg = -1e30f;
+                    for (int sp = 0; sp < S; ++sp) mg = fmaxf(mg, ml[sp * 16 + tid]);
+                    float l = 0.f;
+                    for (int sp = 0; sp < S; ++sp) {
+                        const float f = expf(ml[sp * 16 + tid] - mg);
+                        wl[sp * 16 + tid] = f;
+                        l += f * ml[512 + sp * 16 + tid];
+                    }
+                    wl[S * 16 + tid] = l;
+                }
+                __syncthreads();
+                if (item) {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) v8[q] = 0.f;
+                    const uint32_t eo = uint32_t(32 + row * H + ch * 8) * 4;
+                    for (int sp = 0; sp < S; sp += 2) {
+                        const bool two = sp + 1 < S;
+                        const uint32_t o0 = uint32_t(sp) * PART * 4 + eo, o1 = two ? o0 + PART * 4 : o0;
+                        const uint4v p0 = __builtin_amdgcn_raw_buffer_load_b128(prs, int(o0), 0, kAuxDev);
+                        const uint4v p1 = __builtin_amdgcn_raw_buffer_load_b128(prs, int(o0 + 16), 0, kAuxDev);
+                        const uint4v p2 = __builtin_amdgcn_raw_buffer_load_b128(prs, int(o1), 0, kAuxDev);
+                        const uint4v p3 = __builtin_amdgcn_raw_buffer_load_b128(prs, int(o1 + 16), 0, kAuxDev);
+                        const float f0 = wl[sp * 16 + row], f1 = two ? wl[(sp + 1) * 16 + row] : 0.f;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            v8[q] += f0 * __uint_as_float(p0[q]);
+                            v8[4 + q] += f0 * __uint_as_float(p1[q]);
+                        }
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            v8[q] += f1 * __uint_as_float(p2[q]);
+                            v8[4 + q] += f1 * __uint_as_float(p3[q]);
+                        }
+                    }
+                    inv_l = 1.0f / wl[S * 16 + row];
+                }
+                if (tid == 0)
+                    __hip_atomic_store(&acount[kvh * row_tiles + rt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (finish && item && rr < R) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v8[q] *= inv_l;
+            const int m = rr / G, gl = rr % G;
+            const int k0 = (kvh * G + gl) * H + ch * 8;
+            st_dev_frag8(attfrag_l, frag_index(k0, m, rp), v8);
+        }
+}
+
+// Page buffers per wavefront (K and V fragments of one page and head each): as many as the
+// register file allows next to the query and output tiles.
+template <int H>
+struct AttnBufs {
+    static constexpr int N = H == 128 ? 3 : 4;
+    bf16x8 k[N][H / 32];
+    short4v v[N][H / 16];
+};
+
+// Before the barrier: issue the loads of the first task's first four pages where those hold old
+// context only (they do not depend on this layer's QKV phase).  loaded[i] tells the phase.
+template <int H>
+__device__ __forceinline__ void attn_preload(const MegaArgs& a, int layer, int wave, int lane, int wg, AttnBufs<H>& bf,
+                                             bool (&loaded)[4]) {
+    constexpr int NBUF = AttnBufs<H>::N;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) loaded[i] = false;
+    if (wg >= a.Hkv * a.row_tiles * a.a_splits) return;
+    const AttnTask t = attn_task(a, wg);
+    const __bf16* kpool = a.kpool + size_t(layer) * a.pool_layer_elems;
+    const __bf16* vpool = a.vpool + size_t(layer) * a.pool_layer_elems;
+#pragma unroll
+    for (int i = 0; i < NBUF; ++i) {
+        const int pg = t.pg0 + wave + i * kMegaWaves;
+        if (pg < t.pg1 && (pg + 1) * 16 <= a.ctx_len) {
+            attn_load_page<H>(a, kpool, vpool, t.kvh, pg, lane, bf.k[i], bf.v[i]);
+            loaded[i] = true;
+        }
+    }
+}
+
+template <int H>
+__device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSmem& sm, int wave, int lane, int wg,
+                                           AttnBufs<H>& bf, bool (&loaded)[4]) {
+    constexpr int ST = H / 32, HT = H / 16, PART = 16 * (H + 2), NBUF = AttnBufs<H>::N;
+    const int tid = threadIdx.x;
+    const int R = a.G * a.r;
+    const int col = lane & 15, kq = lane >> 4;
+    const __bf16* kpool = a.kpool + size_t(layer) * a.pool_layer_elems;
+    const __bf16* vpool = a.vpool + size_t(layer) * a.pool_layer_elems;
+    const int n_tasks = a.Hkv * a.row_tiles * a.a_splits;
+    for (int task = wg; task < n_tasks; task += a.nwg) {
+        const AttnTask t = attn_task(a, task);
+        const int kvh = t.kvh, rt = t.rt;
+        const int rho = rt * 16 + col;
+        const bool row_ok = rho < R;
+        const int mrow = row_ok ? rho / a.G : -1;
+        const int limit = a.ctx_len + mrow;  // last visible position of this lane's row
+        int pg = t.pg0 + wave;
+#pragma unroll
+        for (int i = 0; i < NBUF; ++i) {
+            const int pgi = pg + i * kMegaWaves;
+            if (pgi < t.pg1 && !(task == wg && loaded[i]))
+                attn_load_page<H>(a, kpool, vpool, kvh, pgi, lane, bf.k[i], bf.v[i]);
+        }
+        bf16x8 qh[ST], ql[ST];
+        {
+            const bf16x8* qp = reinterpret_cast<const bf16x8*>(
+                a.qfrag + size_t(layer) * a.qfrag_stride + ((size_t(kvh) * (a.G * kMaxR) + (row_ok ? rho : 0)) * (H >> 3)) * 16);
+#pragma unroll
+            for (int st = 0; st < ST; ++st) {
+                qh[st] = qp[(st * 4 + kq) * 2];
+                ql[st] = qp[(st * 4 + kq) * 2 + 1];
+            }
+        }
+        floatx4 o[HT];
+#pragma unroll
+        for (int i = 0; i < HT; ++i) o[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        float mx = -1e30f, sum = 0.f;
+
+        auto use_page = [&](int pgi, const bf16x8 (&kf)[ST], const short4v (&vf)[HT]) {
+            floatx4 sc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int st = 0; st < ST; ++st) {
+                sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[st], qh[st], sc, 0, 0, 0);
+                sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[st], ql[st], sc, 0, 0, 0);
+            }
+            float pmax = -1e30f;
+            bool ok[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                ok[v] = mrow >= 0 && (pgi * 16 + kq * 4 + v) <= limit;
+                if (ok[v]) pmax = fmaxf(pmax, sc[v]);
+            }
+            pmax = fmaxf(pmax, __shfl_xor(pmax, 16));
+            pmax = fmaxf(pmax, __shfl_xor(pmax, 32));
+            const float mnew = fmaxf(mx, pmax);
+            const float alpha = expf(mx - mnew);
+            float pr[4], psum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                pr[v] = ok[v] ? expf(sc[v] - mnew) : 0.f;
+                psum += pr[v];
+            }
+            psum += __shfl_xor(psum, 16);
+            psum += __shfl_xor(psum, 32);
+            sum = sum * alpha + psum;
+            mx = mnew;
+            short4v ph, pl;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                __bf16 hi, lo;
+                split_bf16(pr[v], hi, lo);
+                ph[v] = __builtin_bit_cast(short, hi);
+                pl[v] = __builtin_bit_cast(short, lo);
+            }
+#pragma unroll
+            for (int i = 0; i < HT; ++i) {
+                floatx4 acc = o[i];
+                acc[0] *= alpha; acc[1] *= alpha; acc[2] *= alpha; acc[3] *= alpha;
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[i], ph, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[i], pl, acc, 0, 0, 0);
+                o[i] = acc;
+            }
+        };
+        if (a.ts && layer == a.ts_layer && tid == 0) a.ts[size_t(wg) * 32 + 13] = wall_clock64();
+        // buffers in rotation: NBUF - 1 pages stay in flight behind the one in use
+        while (pg < t.pg1) {
+#pragma unroll
+            for (int i = 0; i < NBUF; ++i) {
+                if (pg < t.pg1) {
+                    use_page(pg, bf.k[i], bf.v[i]);
+                    const int nx = pg + NBUF * kMegaWaves;
+                    if (nx < t.pg1) attn_load_page<H>(a, kpool, vpool, kvh, nx, lane, bf.k[i], bf.v[i]);
+                }
+                pg += kMegaWaves;
+            }
+        }
+
+        if (a.ts && layer == a.ts_layer && tid == 0) a.ts[size_t(wg) * 32 + 14] = wall_clock64();
+        // wavefront partials -> LDS: M[16], L[16], O[16][H]
+        float* mine = sm.attn + wave * PART;
+        if (kq == 0) {
+            mine[col] = mx;
+            mine[16 + col] = sum;
+        }
+#pragma unroll
+        for (int i = 0; i < HT; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mine[32 + col * H + i * 16 + kq * 4 + v] = o[i][v];
+        __syncthreads();
+        if (a.ts && layer == a.ts_layer && tid == 0) a.ts[size_t(wg) * 32 + 15] = wall_clock64();
+        attn_finish<H>(sm, a.apart, a.acount, a.attfrag + size_t(layer) * a.attfrag_stride, a.G, a.rp, R, a.a_splits,
+                       a.row_tiles, task, t.split, kvh, rt);
+        __syncthreads();
+    }
+}
+
+// The attention part of a layer, out of line: it has nothing in common with the GEMM phases
+// (the weight ring is empty while it runs), so it gets a register allocation of its own instead
+// of pushing the streaming loops into spills.  Arguments come straight from the kernel-argument
+// segment.  Returns the barrier generation.
+template <int H>
+__device__ __attribute__((noinline)) uint32_t attention_block(const MegaArgs* ap, int l, MegaSmem* smp, uint32_t gen) {
+    const MegaArgs& a = *ap;
+    MegaSmem& sm = *smp;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wg = blockIdx.x;
+    const bool tsl = a.ts && l == a.ts_layer && tid == 0;
+    if (tsl) a.ts[size_t(wg) * 32 + 16] = wall_clock64();
+    store_wait<0>();  // the QKV phase's stores (queries, new K and V rows)
+    if (tsl) a.ts[size_t(wg) * 32 + 11] = wall_clock64();
+    AttnBufs<H> bf;
+    bool loaded[4];
+    attn_preload<H>(a, l, wave, lane, wg, bf, loaded);
+    if (tsl) a.ts[size_t(wg) * 32 + 12] = wall_clock64();
+    grid_wait(a, gen, sm);
+    if (tsl) a.ts[size_t(wg) * 32 + 2] = wall_clock64();
+    attn_phase<H>(a, l, sm, wave, lane, wg, bf, loaded);
+    return gen;
+}
+
+// ---- the kernel ----------------------------------------------------------------------------------
+template <int MT, int H>
+__global__ __launch_bounds__(kMegaThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_verify(MegaArgs a) {
+    __shared__ MegaSmem sm;
+    constexpr int NB_QKV = 2, NB_ONE = 1, NB_WIDE = MT == 1 ? 8 : 4;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wg = blockIdx.x, nwg = a.nwg;
+    uint32_t gen = 0;
+    if (tid == 0) {
+        sm.failed = 0;
+        sm.epoch = __hip_atomic_load(&a.bar[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (tid < kMaxR) sm.wg_best[tid] = 0ull;
+    __syncthreads();
+
+    const int n_dt = a.d >> 4;  // 16-column tiles of the residual stream
+    auto layer_base = [&](int l) { return a.wbase + a.layer0_off + size_t(l) * a.layer_stride; };
+    auto mat = [&](const char* base, const MatDesc& m) { return reinterpret_cast<const bf16x8*>(base + m.off); };
+
+    bf16x8 ring[kRing];
+    // start the weight ring on layer 0's QKV matrix before anything else
+    PhasePlan p_qkv = plan_phase(mat(layer_base(0), a.qkv), a.qkv.Nt, a.qkv.Ks, wg, nwg, 0, wave);
+    ring_fill(ring, first_src<NB_QKV>(p_qkv, nwg), lane);
+
+    // ---- embed: x0 = E[token], its gained high/low fragments, per-tile sums of squares ----
+    {
+        const __bf16* E = reinterpret_cast<const __bf16*>(a.wbase + a.embed_off);
+        const float* g0 = reinterpret_cast<const float*>(layer_base(0) + a.g_attn_off);
+        constexpr int TP = kMegaThreads / (2 * kMaxR);  // tiles per pass
+        const int c = tid & 1, m = (tid >> 1) % kMaxR, i = tid / (2 * kMaxR);
+        for (int t = wg * TP + i; t < n_dt; t += nwg * TP) {
+            float ssum = 0.f;
+            const bool on = m < a.r;
+            if (on) {
+                int tok = a.cand[m];
+                tok = tok < 0 ? 0 : (tok >= a.V ? a.V - 1 : tok);
+                const int n0 = t * 16 + c * 8;
+                const bf16x8 ev = *reinterpret_cast<const bf16x8*>(E + size_t(tok) * a.d + n0);
+                float nv[8], gv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    nv[e] = static_cast<float>(ev[e]);
+                    ssum += nv[e] * nv[e];
+                    gv[e] = nv[e] * g0[n0 + e];
+                }
+                st_dev_f32x8(a.xres, uint32_t(m) * a.d + n0, nv);
+                st_dev_frag8(a.xfrag, frag_index(n0, m, a.rp), gv);
+            }
+            ssum += __shfl_xor(ssum, 1);
+            if (on && c == 0) st_agent(a.ss + size_t(t) * kMaxR + m, ssum);
+        }
+        // rotation table in fp64 (long contexts stay exact), spread over the grid
+        const int half = a.h >> 1;
+        for (int e = wg * kMegaThreads + tid; e < a.r * half; e += nwg * kMegaThreads) {
+            const int m2 = e / half, j = e % half;
+            const double ang = double(a.ctx_len + m2) * pow(double(a.theta), -2.0 * j / a.h);
+            st_agent(a.rope + m2 * half + j, float(cos(ang)));
+            st_agent(a.rope + kMaxR * half + m2 * half + j, float(sin(ang)));
+        }
+        if (wg == 0 && tid < kMaxR)
+            __hip_atomic_store(&a.best[tid], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    store_wait<0>();  // the embed stores are younger than the first ring fill
+    grid_wait(a, gen, sm);
+
+    const size_t xres_stride = size_t(kMaxR) * a.d, ss_stride = size_t(n_dt) * kMaxR;
+    // end of a GEMM phase whose ring runs ahead into `nx`: wait for the stores only, cross the
+    // barrier, then let the polling wavefront catch up on the half of the ring it held back
+    auto phase_end = [&](const RingSrc& nx) {
+        if (wave == 0)
+            store_wait<0>();
+        else
+            store_wait<kRing / 2>();
+        grid_wait(a, gen, sm);
+        if (wave == 0) ring_fill_half<1>(ring, nx, lane);
+    };
+#define CARD_TS(i)                                                                  \
+    if (a.ts && l == a.ts_layer && tid == 0) a.ts[size_t(wg) * 32 + (i)] = wall_clock64();
+    for (int l = 0; l < a.L; ++l) {
+        const char* lb = layer_base(l);
+        const int v0 = 2 * l, v1 = 2 * l + 1, v2 = 2 * l + 2;
+        const bool last = l + 1 == a.L;
+        EpiArgs ea = {};
+        ea.layer = l;
+
+        // QKV (+norm scale, rotation, KV write); the ring runs on into the O-projection
+        PhasePlan p_wo = plan_phase(mat(lb, a.wo), a.wo.Nt, a.wo.Ks, wg, nwg, (l & 1) * (nwg / 2), wave);
+        ea.ss_in = a.ss + v0 * ss_stride;
+        ea.qfrag = a.qfrag + size_t(l) * a.qfrag_stride;
+        ea.kpool = a.kpool + size_t(l) * a.pool_layer_elems;
+        ea.vpool = a.vpool + size_t(l) * a.pool_layer_elems;
+        CARD_TS(0)
+        gemm_phase<NB_QKV, MT, ME_QKV, false>(a, p_qkv, a.xfrag + v0 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea,
+                                              ring, first_src<NB_ONE>(p_wo, nwg), sm, wave, lane);
+        CARD_TS(1)
+        gen = attention_block<H>((const MegaArgs*)__builtin_amdgcn_kernarg_segment_ptr(), l, &sm, gen);
+        // the ring was empty during attention; start it on the O-projection behind the stores
+        // (the wavefront that polls the barrier fills its ring only after the barrier)
+        if (wave != 0) ring_fill(ring, first_src<NB_ONE>(p_wo, nwg), lane);
+        CARD_TS(3)
+        if (wave == 0) store_wait<0>(); else store_wait<kRing>();
+        grid_wait(a, gen, sm);
+        if (wave == 0) ring_fill(ring, first_src<NB_ONE>(p_wo, nwg), lane);
+        CARD_TS(4)
+
+        // O-projection + residual -> version v1, gained with the FFN norm's gain
+        PhasePlan p_gu = plan_phase(mat(lb, a.gu), a.gu.Nt, a.gu.Ks, wg, nwg, 0, wave);
+        ea.xres_old = a.xres + v0 * xres_stride;
+        ea.xres_new = a.xres + v1 * xres_stride;
+        ea.xfrag_new = a.xfrag + v1 * a.xfrag_stride;
+        ea.ss_new = a.ss + v1 * ss_stride;
+        ea.gain_next = reinterpret_cast<const float*>(lb + a.g_ffn_off);
+        gemm_phase<NB_ONE, MT, ME_RESID>(a, p_wo, a.attfrag + size_t(l) * a.attfrag_stride, uint32_t(a.attfrag_stride * 2), ea, ring,
+                                         first_src<NB_WIDE>(p_gu, nwg), sm, wave, lane);
+        CARD_TS(5)
+        phase_end(first_src<NB_WIDE>(p_gu, nwg));
+        CARD_TS(6)
+
+        // gate/up + SwiGLU
+        PhasePlan p_wd = plan_phase(mat(lb, a.wd), a.wd.Nt, a.wd.Ks, wg, nwg, ((l + 1) & 1) * (nwg / 2), wave);
+        ea.ss_in = a.ss + v1 * ss_stride;
+        ea.actfrag = a.actfrag + size_t(l) * a.actfrag_stride;
+        gemm_phase<NB_WIDE, MT, ME_SWIGLU>(a, p_gu, a.xfrag + v1 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea, ring, first_src<NB_ONE>(p_wd, nwg),
+                                           sm, wave, lane);
+        CARD_TS(7)
+        phase_end(first_src<NB_ONE>(p_wd, nwg));
+        CARD_TS(8)
+
+        // down + residual -> version v2, gained with the next norm's gain
+        ea.xres_old = a.xres + v1 * xres_stride;
+        ea.xres_new = a.xres + v2 * xres_stride;
+        ea.xfrag_new = a.xfrag + v2 * a.xfrag_stride;
+        ea.ss_new = a.ss + v2 * ss_stride;
+        ea.gain_next = last ? reinterpret_cast<const float*>(a.wbase + a.g_final_off)
+                            : reinterpret_cast<const float*>(layer_base(l + 1) + a.g_attn_off);
+        if (!last) {
+            p_qkv = plan_phase(mat(layer_base(l + 1), a.qkv), a.qkv.Nt, a.qkv.Ks, wg, nwg, ((l + 1) & 1) * (nwg / 2),
+                               wave);
+            gemm_phase<NB_ONE, MT, ME_RESID>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride, uint32_t(a.actfrag_stride * 2), ea, ring,
+                                             first_src<NB_QKV>(p_qkv, nwg), sm, wave, lane);
+            CARD_TS(9)
+            phase_end(first_src<NB_QKV>(p_qkv, nwg));
+        } else {
+            PhasePlan p_lm = plan_phase(mat(a.wbase, a.lm), a.lm.Nt, a.lm.Ks, wg, nwg, 0, wave);
+            gemm_phase<NB_ONE, MT, ME_RESID>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride, uint32_t(a.actfrag_stride * 2), ea, ring,
+                                             first_src<NB_WIDE>(p_lm, nwg), sm, wave, lane);
+            phase_end(first_src<NB_WIDE>(p_lm, nwg));
+        }
+        CARD_TS(10)
+    }
+
+    // vocabulary head + arg-max; nothing follows, the ring refills from the matrix start (harmless)
+    {
+        PhasePlan p_lm = plan_phase(mat(a.wbase, a.lm), a.lm.Nt, a.lm.Ks, wg, nwg, 0, wave);
+        EpiArgs ea = {};
+        ea.ss_in = a.ss + size_t(2 * a.L) * ss_stride;
+        RingSrc idle = first_src<NB_WIDE>(p_lm, nwg);
+        gemm_phase<NB_WIDE, MT, ME_LM>(a, p_lm, a.xfrag + size_t(2 * a.L) * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea, ring, idle, sm,
+                                       wave, lane);
+        if (tid < a.r && sm.wg_best[tid] != 0ull)
+            __hip_atomic_fetch_max(&a.best[tid], sm.wg_best[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    store_wait<0>();
+    grid_wait(a, gen, sm);
+
+    // keep the last ring loads alive until they have landed (they are never consumed)
+    {
+        float sink = 0.f;
+#pragma unroll
+        for (int idx = 0; idx < kRing; ++idx) sink += static_cast<float>(ring[idx][0]);
+        if (sink == 1.2345e-30f) a.rope[0] = sink;
+    }
+
+    if (wg == 0) {
+        __shared__ int pred[kMaxR + 1];
+        if (tid < a.r) {
+            const unsigned long long k = __hip_atomic_load(&a.best[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            pred[tid + 1] = int(0xffffffffu - uint32_t(k & 0xffffffffull));
+        }
+        __syncthreads();
+        if (tid == 0) {
+            pred[0] = a.pending < 0 ? a.cand[0] : a.pending;
+            int j = 0;
+            while (j < a.r && a.cand[j] == pred[j]) ++j;
+            const bool failed = sm.failed || __hip_atomic_load(&a.bar[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+            a.out->accepted_len = failed ? -1 : j;
+            a.out->correction_token = failed ? -1 : pred[j];
+            a.out->kv_first_slot = a.ctx_len;
+            a.out->kv_count = failed ? 0 : j;
+        }
+        if (a.row_argmax && tid < a.r) a.row_argmax[tid] = pred[tid + 1];
+    }
+    // the last workgroup to leave re-arms the counters for the next call
+    if (tid == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(&a.bar[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev == uint32_t(nwg) - 1) {
+            // barrier sequence numbers of the next call start above anything this call used
+            __hip_atomic_store(&a.bar[3], sm.epoch + 8192u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.bar[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.bar[2], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+}  // namespace card
