@@ -92,8 +92,8 @@ int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t 
  * Paged KV cache of the target model (bf16).  k_pages / v_pages each hold
  * card_kv_pool_bytes(cfg, n_pages) bytes; page p of layer l starts at
  * ((l * n_pages + p) * n_kv_heads) * 16 * head_dim elements.  Token position t lives in page
- * block_table[t / 16], slot t % 16.  Inside a page K is stored after rotation, in
- * [head_dim/8][16 tokens][8] order, V in [head_dim][16 tokens] order (use card_kv_gather to
+ * block_table[t / 16], slot t % 16.  Inside a page both K (after rotation) and V are stored in
+ * the operand order of the gfx950 matrix instructions that consume them (use card_kv_gather to
  * read them back in plain order).
  * ---------------------------------------------------------------------------------------- */
 typedef struct card_kv {
@@ -125,10 +125,14 @@ typedef struct card_verify_result {
  *   packed_weights_dev : blob filled by card_weights_pack_tensor
  *   kv                 : host struct (read during the call only)
  *   cand_tokens_dev    : dev, r int32 token ids in [0, vocab)
- *   workspace_dev      : dev, card_workspace_bytes(cfg) bytes, contents irrelevant on entry
- *                        except that the caller zeroes it once after allocation
+ *   workspace_dev      : dev, card_workspace_bytes(cfg) bytes; the caller zeroes it once after
+ *                        allocation (and again after a call reported CARD_EDEVICE or
+ *                        accepted_len < 0); calls sharing a workspace must not overlap
  *   out_dev            : dev (or device-visible pinned host) card_verify_result
  *   row_argmax_dev     : dev, optional (may be NULL): r int32, arg-max of each row
+ * The step runs as one persistent cooperative kernel (one workgroup per compute unit) whose
+ * grid barriers have a bounded wait: should the grid ever fail to meet (it cannot when the
+ * device is otherwise idle), the kernel still terminates and reports accepted_len = -1.
  * Errors: CARD_EINVAL, CARD_ERANGE (r), CARD_ECAPACITY (ctx_len + r > max_ctx); nothing is
  * enqueued on error.  Token ids are not range-checked on the host (they are on the device:
  * an id outside [0, vocab) is clamped). */
@@ -144,17 +148,18 @@ int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weigh
                              card_verify_result* out_dev, int32_t* row_argmax_dev,
                              float* logits_dev);
 
-/* Measurement hook (benchmark only).  While enabled, card_verify brackets every launch of one
- * kernel kind with a pair of HIP events recorded on the call's stream, up to max_launches
- * pairs; card_profile_collect waits for them, writes each launch's duration in milliseconds
- * to ms_host (host array of max_launches floats), returns the count in *n_host and disables
- * the hook.  Not thread-safe; creates HIP events, allocates no device memory. */
-typedef enum card_kernel_kind {
-    CARD_K_QKV = 0, CARD_K_ATTN = 1, CARD_K_WO = 2, CARD_K_GATE_UP = 3, CARD_K_DOWN = 4, CARD_K_LM_HEAD = 5,
-    CARD_K_STEP = 6
-} card_kernel_kind;
-int card_profile_enable(int32_t kind, int32_t max_launches);
+/* Measurement hooks (benchmark only; not thread-safe; allocate no device memory).
+ * card_profile_enable: while enabled, card_verify brackets its kernel with a pair of HIP
+ * events recorded on the call's stream, up to max_launches pairs; card_profile_collect waits
+ * for them, writes each launch's duration in milliseconds to ms_host (host array of
+ * max_launches floats), returns the count in *n_host and disables the hook.
+ * card_profile_timeline: buf_dev = device array of 32 uint64 per workgroup (256 workgroups), or
+ * NULL to switch off; while set, the verify kernel stores 100 MHz timestamps of the phase
+ * boundaries of decoder layer `layer` there (start, QKV done, barrier, attention done, barrier,
+ * O-proj done, barrier, gate/up done, barrier, down done, barrier). */
+int card_profile_enable(int32_t max_launches);
 int card_profile_collect(float* ms_host, int32_t* n_host);
+int card_profile_timeline(void* buf_dev, int32_t layer);
 
 /* Test helper: copies K (rotated) and V of positions [first_slot, first_slot+count) of one
  * layer out of the paged cache into plain fp32 arrays [count][n_kv_heads][head_dim] (dev). */

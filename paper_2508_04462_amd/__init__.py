@@ -29,7 +29,7 @@ from .binding import (  # noqa: F401
     card_kv_gather,
     card_profile_enable,
     card_profile_collect,
-    KERNEL_KINDS,
+    card_profile_timeline,
     card_cache_create,
     card_cache_destroy,
     card_cache_write,

@@ -77,7 +77,9 @@ lib.card_verify_debug_logits.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int
 lib.card_kv_gather.restype = C.c_int
 lib.card_kv_gather.argtypes = [_cfgp, _kvp, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P]
 lib.card_profile_enable.restype = C.c_int
-lib.card_profile_enable.argtypes = [C.c_int32, C.c_int32]
+lib.card_profile_enable.argtypes = [C.c_int32]
+lib.card_profile_timeline.restype = C.c_int
+lib.card_profile_timeline.argtypes = [_P, C.c_int32]
 lib.card_profile_collect.restype = C.c_int
 lib.card_profile_collect.argtypes = [_f32p, _i32p]
 lib.card_cache_create.restype = C.c_int
@@ -146,11 +148,12 @@ def card_kv_gather(cfg, kv: CardKV, layer: int, first_slot: int, count: int, k_o
                               _ptr(v_out_dev), _ptr(stream))
 
 
-KERNEL_KINDS = {"qkv": 0, "attn": 1, "wo": 2, "gate_up": 3, "down": 4, "lm_head": 5}
+def card_profile_enable(max_launches: int) -> int:
+    return lib.card_profile_enable(max_launches)
 
 
-def card_profile_enable(kind: int, max_launches: int) -> int:
-    return lib.card_profile_enable(kind, max_launches)
+def card_profile_timeline(buf_dev, layer: int) -> int:
+    return lib.card_profile_timeline(_ptr(buf_dev), layer)
 
 
 def card_profile_collect(max_launches: int):

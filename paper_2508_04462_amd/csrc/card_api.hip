@@ -4,8 +4,8 @@
 #include <vector>
 
 #include "card.h"
-#include "card_kernels.hip"
-#include "card_mega.hip"
+#include "card_pack.hip"
+#include "card_verify.hip"
 
 using namespace card;
 
@@ -17,11 +17,10 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? CARD_OK : 
 
 unsigned long long* g_ts_buf = nullptr;
 int g_ts_layer = 0;
-bool g_use_mega = true;  // TEMPORARY while the persistent kernel is brought up
 
-// benchmark hook: event pairs around one kernel kind
+// benchmark hook: event pairs around the verify kernel
 struct Profile {
-    int kind = -1;
+    bool on = false;
     int used = 0;
     std::vector<hipEvent_t> start, stop;
 };
@@ -30,8 +29,8 @@ Profile g_prof;
 struct ProfScope {
     hipStream_t st;
     int idx = -1;
-    ProfScope(int kind, hipStream_t s) : st(s) {
-        if (g_prof.kind == kind && g_prof.used < int(g_prof.start.size())) {
+    explicit ProfScope(hipStream_t s) : st(s) {
+        if (g_prof.on && g_prof.used < int(g_prof.start.size())) {
             idx = g_prof.used++;
             (void)hipEventRecord(g_prof.start[idx], st);
         }
@@ -40,40 +39,6 @@ struct ProfScope {
         if (idx >= 0) (void)hipEventRecord(g_prof.stop[idx], st);
     }
 };
-
-template <int MT>
-int launch_gemm(int epi, const GemmArgs& a, const GemmPlan& p, hipStream_t st) {
-    const dim3 grid(p.groups * p.splits), block(kGemmWaves * 64);
-    switch (epi) {
-        case EPI_QKV: hipLaunchKernelGGL((k_gemm<MT, EPI_QKV>), grid, block, 0, st, a); break;
-        case EPI_RESID: hipLaunchKernelGGL((k_gemm<MT, EPI_RESID>), grid, block, 0, st, a); break;
-        case EPI_SWIGLU: hipLaunchKernelGGL((k_gemm<MT, EPI_SWIGLU>), grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL((k_gemm<MT, EPI_LMHEAD>), grid, block, 0, st, a); break;
-    }
-    return launch_status();
-}
-
-int gemm(int epi, int r, const GemmArgs& a, const GemmPlan& p, hipStream_t st) {
-    return r <= 16 ? launch_gemm<1>(epi, a, p, st) : launch_gemm<2>(epi, a, p, st);
-}
-
-GemmArgs base_args(const char* wbase, const MatDesc& m, const GemmPlan& p, const float* xin, int ldx, int r,
-                   char* ws, const Layout& L) {
-    GemmArgs a = {};
-    a.w = reinterpret_cast<const bf16x8*>(wbase + m.off);
-    a.N = m.N;
-    a.K = m.K;
-    a.Nt = m.Nt;
-    a.Ks = m.Ks;
-    a.splits = p.splits;
-    a.steps_per_split = p.steps_per_split;
-    a.xin = xin;
-    a.ldx = ldx;
-    a.r = r;
-    a.part = reinterpret_cast<float*>(ws + L.part_off);
-    a.counters = reinterpret_cast<int32_t*>(ws + L.cnt_off);
-    return a;
-}
 
 int cu_count() {
     static int cus = 0;
@@ -94,8 +59,8 @@ int launch_mega(MegaArgs& a, hipStream_t st) {
     return e == hipSuccess ? CARD_OK : CARD_EDEVICE;
 }
 
-// One persistent cooperative kernel runs the whole step.
-int verify_mega(const card_model_cfg* cfg, const void* packed, const card_kv* kv, int32_t ctx_len,
+// One persistent cooperative kernel runs the whole step (card_verify.hip).
+int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv, int32_t ctx_len,
                 const int32_t* cand, int32_t r, void* workspace, void* stream, card_verify_result* out,
                 int32_t* row_argmax, float* logits) {
     if (!cfg || !packed || !kv || !cand || !workspace || !out) return CARD_EINVAL;
@@ -177,173 +142,9 @@ int verify_mega(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.ts = g_ts_buf;
     a.ts_layer = g_ts_layer;
     hipStream_t st = as_stream(stream);
-    ProfScope ps(CARD_K_STEP, st);
+    ProfScope ps(st);
     if (r <= 16) return h == 128 ? launch_mega<1, 128>(a, st) : launch_mega<1, 64>(a, st);
     return h == 128 ? launch_mega<2, 128>(a, st) : launch_mega<2, 64>(a, st);
-}
-
-int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv, int32_t ctx_len,
-                const int32_t* cand, int32_t r, void* workspace, void* stream, card_verify_result* out,
-                int32_t* row_argmax, float* logits) {
-    if (!cfg || !packed || !kv || !cand || !workspace || !out) return CARD_EINVAL;
-    const Layout L = make_layout(cfg);
-    if (!L.ok) return CARD_EINVAL;
-    if (!kv->k_pages || !kv->v_pages || !kv->block_table || kv->n_pages <= 0) return CARD_EINVAL;
-    if (r < 1 || r > cfg->max_r) return CARD_ERANGE;
-    if (ctx_len < 0) return CARD_EINVAL;
-    if (int64_t(ctx_len) + r > cfg->max_ctx) return CARD_ECAPACITY;
-
-    hipStream_t st = as_stream(stream);
-    const char* wb = static_cast<const char*>(packed);
-    char* ws = static_cast<char*>(workspace);
-    const int d = cfg->d_model, h = cfg->head_dim, qd = cfg->n_q_heads * h, kvd = cfg->n_kv_heads * h;
-    const int G = cfg->n_q_heads / cfg->n_kv_heads;
-    float* x = reinterpret_cast<float*>(ws + L.x_off);
-    float* q = reinterpret_cast<float*>(ws + L.q_off);
-    float* att = reinterpret_cast<float*>(ws + L.att_off);
-    float* act = reinterpret_cast<float*>(ws + L.act_off);
-    float* ss = reinterpret_cast<float*>(ws + L.ss_off);
-    float* rope = reinterpret_cast<float*>(ws + L.rope_off);
-    int32_t* acnt = reinterpret_cast<int32_t*>(ws + L.acnt_off);
-    const float inv_d = 1.0f / float(d);
-
-    // attention decomposition
-    const int row_tiles = ceil_div(G * r, 16), row_pairs = ceil_div(row_tiles, 2);
-    const int pages_used = ceil_div(ctx_len + r, kKvBlock);
-    int a_splits = ceil_div(256, cfg->n_kv_heads * row_pairs);
-    const int max_by_pages = ceil_div(pages_used, kAttnWaves);
-    if (a_splits > max_by_pages) a_splits = max_by_pages;
-    if (a_splits > L.attn_max_splits) a_splits = L.attn_max_splits;
-    if (a_splits < 1) a_splits = 1;
-    const int pages_per_split = ceil_div(pages_used, a_splits);
-    a_splits = ceil_div(pages_used, pages_per_split);
-
-    {
-        EmbedArgs e = {};
-        e.embed = reinterpret_cast<const __bf16*>(wb + L.embed_off);
-        e.tokens = cand;
-        e.r = r;
-        e.d = d;
-        e.vocab = cfg->vocab;
-        e.x = x;
-        e.ss_out = ss;
-        e.rope = rope;
-        e.ctx_len = ctx_len;
-        e.head_dim = h;
-        e.theta = cfg->rope_theta;
-        e.counters = reinterpret_cast<int32_t*>(ws + L.cnt_off);
-        e.n_counters = L.n_counters;
-        e.acounters = acnt;
-        e.n_acounters = cfg->n_kv_heads * ceil_div(L.attn_row_tiles_max, 2);
-        e.best = reinterpret_cast<unsigned long long*>(ws + L.best_off);
-        hipLaunchKernelGGL(k_embed, dim3(d / 64), dim3(64), 0, st, e);
-        if (launch_status() != CARD_OK) return CARD_EDEVICE;
-    }
-
-    const size_t pool_layer_elems = size_t(kv->n_pages) * cfg->n_kv_heads * 16 * h;
-    for (int l = 0; l < cfg->n_layers; ++l) {
-        const char* lb = wb + L.layer0_off + size_t(l) * L.layer_stride;
-        __bf16* kpool = static_cast<__bf16*>(kv->k_pages) + size_t(l) * pool_layer_elems;
-        __bf16* vpool = static_cast<__bf16*>(kv->v_pages) + size_t(l) * pool_layer_elems;
-        {
-            GemmArgs a = base_args(lb, L.qkv, L.p_qkv, x, d, r, ws, L);
-            a.gain = reinterpret_cast<const float*>(lb + L.g_attn_off);
-            a.ss_in = ss;
-            a.ss_in_groups = L.ss_groups;
-            a.inv_d = inv_d;
-            a.eps = cfg->rms_eps;
-            a.q = q;
-            a.kpool = kpool;
-            a.vpool = vpool;
-            a.block_table = kv->block_table;
-            a.rope = rope;
-            a.ctx_len = ctx_len;
-            a.head_dim = h;
-            a.q_dim = qd;
-            a.kv_dim = kvd;
-            a.n_kv_heads = cfg->n_kv_heads;
-            ProfScope ps(CARD_K_QKV, st);
-            if (gemm(EPI_QKV, r, a, L.p_qkv, st) != CARD_OK) return CARD_EDEVICE;
-        }
-        {
-            AttnArgs a = {};
-            a.q = q;
-            a.kpool = kpool;
-            a.vpool = vpool;
-            a.block_table = kv->block_table;
-            a.r = r;
-            a.G = G;
-            a.n_kv_heads = cfg->n_kv_heads;
-            a.q_dim = qd;
-            a.ctx_len = ctx_len;
-            a.n_pages_used = pages_used;
-            a.splits = a_splits;
-            a.pages_per_split = pages_per_split;
-            a.row_pairs = row_pairs;
-            a.inv_sqrt_h = 1.0f / sqrtf(float(h));
-            a.part = reinterpret_cast<float*>(ws + L.apart_off);
-            a.counters = acnt;
-            a.att = att;
-            ProfScope ps(CARD_K_ATTN, st);
-            const dim3 grid(cfg->n_kv_heads * row_pairs * a_splits), block(kAttnWaves * 64);
-            if (h == 128)
-                hipLaunchKernelGGL(k_attn<128>, grid, block, 0, st, a);
-            else
-                hipLaunchKernelGGL(k_attn<64>, grid, block, 0, st, a);
-            if (launch_status() != CARD_OK) return CARD_EDEVICE;
-        }
-        {
-            GemmArgs a = base_args(lb, L.wo, L.p_wo, att, qd, r, ws, L);
-            a.x = x;
-            a.ss_out = ss;
-            ProfScope ps(CARD_K_WO, st);
-            if (gemm(EPI_RESID, r, a, L.p_wo, st) != CARD_OK) return CARD_EDEVICE;
-        }
-        {
-            GemmArgs a = base_args(lb, L.gu, L.p_gu, x, d, r, ws, L);
-            a.gain = reinterpret_cast<const float*>(lb + L.g_ffn_off);
-            a.ss_in = ss;
-            a.ss_in_groups = L.ss_groups;
-            a.inv_d = inv_d;
-            a.eps = cfg->rms_eps;
-            a.act = act;
-            a.F = cfg->d_ffn;
-            ProfScope ps(CARD_K_GATE_UP, st);
-            if (gemm(EPI_SWIGLU, r, a, L.p_gu, st) != CARD_OK) return CARD_EDEVICE;
-        }
-        {
-            GemmArgs a = base_args(lb, L.wd, L.p_wd, act, cfg->d_ffn, r, ws, L);
-            a.x = x;
-            a.ss_out = ss;
-            ProfScope ps(CARD_K_DOWN, st);
-            if (gemm(EPI_RESID, r, a, L.p_wd, st) != CARD_OK) return CARD_EDEVICE;
-        }
-    }
-    {
-        GemmArgs a = base_args(wb, L.lm, L.p_lm, x, d, r, ws, L);
-        a.gain = reinterpret_cast<const float*>(wb + L.g_final_off);
-        a.ss_in = ss;
-        a.ss_in_groups = L.ss_groups;
-        a.inv_d = inv_d;
-        a.eps = cfg->rms_eps;
-        a.best = reinterpret_cast<unsigned long long*>(ws + L.best_off);
-        a.logits = logits;
-        ProfScope ps(CARD_K_LM_HEAD, st);
-        if (gemm(EPI_LMHEAD, r, a, L.p_lm, st) != CARD_OK) return CARD_EDEVICE;
-    }
-    {
-        AcceptArgs a = {};
-        a.best = reinterpret_cast<const unsigned long long*>(ws + L.best_off);
-        a.r = r;
-        a.cand = cand;
-        a.pending = kv->pending_token;
-        a.ctx_len = ctx_len;
-        a.out = out;
-        a.row_argmax = row_argmax;
-        hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, st, a);
-        if (launch_status() != CARD_OK) return CARD_EDEVICE;
-    }
-    return CARD_OK;
 }
 
 }  // namespace
@@ -432,8 +233,8 @@ int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t 
 int card_verify(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv, int32_t ctx_len,
                 const int32_t* cand_tokens_dev, int32_t r, void* workspace_dev, void* stream,
                 card_verify_result* out_dev, int32_t* row_argmax_dev) {
-    return (g_use_mega ? verify_mega : verify_impl)(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r,
-                                                    workspace_dev, stream, out_dev, row_argmax_dev, nullptr);
+    return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, workspace_dev, stream, out_dev,
+                       row_argmax_dev, nullptr);
 }
 
 int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
@@ -441,30 +242,25 @@ int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weigh
                              void* stream, card_verify_result* out_dev, int32_t* row_argmax_dev,
                              float* logits_dev) {
     if (!logits_dev) return CARD_EINVAL;
-    return (g_use_mega ? verify_mega : verify_impl)(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r,
-                                                    workspace_dev, stream, out_dev, row_argmax_dev, logits_dev);
+    return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, workspace_dev, stream, out_dev,
+                       row_argmax_dev, logits_dev);
 }
 
-int card_debug_timeline(void* buf_dev, int32_t layer) {
+int card_profile_timeline(void* buf_dev, int32_t layer) {
     g_ts_buf = static_cast<unsigned long long*>(buf_dev);
     g_ts_layer = layer;
     return CARD_OK;
 }
 
-int card_debug_use_mega(int on) {
-    g_use_mega = on != 0;
-    return CARD_OK;
-}
-
-int card_profile_enable(int32_t kind, int32_t max_launches) {
-    if (kind < CARD_K_QKV || kind > CARD_K_STEP || max_launches <= 0) return CARD_EINVAL;
+int card_profile_enable(int32_t max_launches) {
+    if (max_launches <= 0) return CARD_EINVAL;
     while (int(g_prof.start.size()) < max_launches) {
         hipEvent_t a, b;
         if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return CARD_EDEVICE;
         g_prof.start.push_back(a);
         g_prof.stop.push_back(b);
     }
-    g_prof.kind = kind;
+    g_prof.on = true;
     g_prof.used = 0;
     return CARD_OK;
 }
@@ -472,7 +268,7 @@ int card_profile_enable(int32_t kind, int32_t max_launches) {
 int card_profile_collect(float* ms_host, int32_t* n_host) {
     if (!ms_host || !n_host) return CARD_EINVAL;
     const int n = g_prof.used;
-    g_prof.kind = -1;
+    g_prof.on = false;
     g_prof.used = 0;
     for (int i = 0; i < n; ++i) {
         if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) return CARD_EDEVICE;

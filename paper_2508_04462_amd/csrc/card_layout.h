@@ -1,5 +1,5 @@
 // Host-side description of where everything lives: the packed weight blob, the workspace,
-// and how each weight-streaming GEMM is cut into tasks.  Plain structs, passed to kernels by value.
+// of the persistent verify kernel.  Plain structs, passed to kernels by value.
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -10,13 +10,7 @@ namespace card {
 
 constexpr int kTileN = 16;     // rows of one matrix-instruction tile (output features)
 constexpr int kTileK = 32;     // contraction depth of one bf16 16x16x32 matrix instruction
-constexpr int kGroupTiles = 4; // n-tiles handled together by one task (64 output features)
-constexpr int kGroupRows = kTileN * kGroupTiles;
 constexpr int kMaxR = 32;
-constexpr int kTargetTasks = 768;  // about three tasks per compute unit of a 256-CU part
-constexpr int kMaxSplits = 16;
-constexpr int kGemmWaves = 4;      // wavefronts per GEMM workgroup
-constexpr int kAttnWaves = 4;
 constexpr int kKvBlock = 16;
 
 // One matrix in tile order: [Nt n-tiles][Ks k-steps][64 lanes][8 bf16]; lane l of tile (t, s)
@@ -27,49 +21,22 @@ struct MatDesc {
     size_t bytes() const { return size_t(Nt) * Ks * 1024; }
 };
 
-struct GemmPlan {
-    int32_t groups;           // ceil(Nt / 4)
-    int32_t splits;           // cuts of the contraction dimension across workgroups
-    int32_t steps_per_split;  // k-steps per cut
-};
-
 struct Layout {
     bool ok;
     // packed weights
     size_t embed_off, lm_off, g_final_off, layer0_off, layer_stride, weight_bytes;
     MatDesc qkv, wo, gu, wd, lm;  // layer matrices relative to the layer base; lm absolute
     size_t g_attn_off, g_ffn_off; // relative to the layer base
-    GemmPlan p_qkv, p_wo, p_gu, p_wd, p_lm;
-    // workspace (byte offsets)
-    size_t x_off, q_off, att_off, act_off, ss_off, part_off, cnt_off, apart_off, acnt_off, best_off,
-        rope_off, ws_bytes;
+    size_t ws_bytes;
     // workspace of the persistent kernel (byte offsets) and strides in elements
     size_t m_xres_off, m_xfrag_off, m_ss_off, m_qfrag_off, m_attfrag_off, m_actfrag_off, m_apart_off, m_bar_off,
         m_acount_off, m_flags_off, m_best_off, m_rope_off;
     size_t xfrag_stride, attfrag_stride, actfrag_stride, qfrag_stride;
     int32_t m_attn_max_splits;
-    int32_t ss_groups;   // rows of the sum-of-squares partial table
-    int32_t n_counters;  // int32 counters for split-K groups
-    int32_t attn_max_splits, attn_row_tiles_max;
 };
 
 inline int32_t ceil_div(int64_t a, int64_t b) { return int32_t((a + b - 1) / b); }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-inline GemmPlan plan_gemm(const MatDesc& m) {
-    GemmPlan p;
-    p.groups = ceil_div(m.Nt, kGroupTiles);
-    int32_t want = ceil_div(kTargetTasks, p.groups);
-    int32_t max_by_k = m.Ks / kGemmWaves;  // keep at least one k-step per wavefront
-    if (max_by_k < 1) max_by_k = 1;
-    int32_t s = want;
-    if (s > kMaxSplits) s = kMaxSplits;
-    if (s > max_by_k) s = max_by_k;
-    if (s < 1) s = 1;
-    p.steps_per_split = ceil_div(m.Ks, s);
-    p.splits = ceil_div(m.Ks, p.steps_per_split);
-    return p;
-}
 
 inline MatDesc make_mat(size_t off, int32_t N, int32_t K) {
     MatDesc m;
@@ -124,13 +91,6 @@ inline Layout make_layout(const card_model_cfg* c) {
     lo = align_up(lo + size_t(d) * 4, 1024);
     L.layer_stride = lo;
     L.weight_bytes = L.layer0_off + size_t(c->n_layers) * L.layer_stride;
-    L.p_qkv = plan_gemm(L.qkv);
-    L.p_wo = plan_gemm(L.wo);
-    L.p_gu = plan_gemm(L.gu);
-    L.p_wd = plan_gemm(L.wd);
-    L.p_lm = plan_gemm(L.lm);
-    L.p_lm.splits = 1;  // the vocabulary head has thousands of groups; never cut its K
-    L.p_lm.steps_per_split = L.lm.Ks;
 
     // workspace
     size_t w = 0;
@@ -139,32 +99,7 @@ inline Layout make_layout(const card_model_cfg* c) {
         w = align_up(w + bytes, 256);
         return at;
     };
-    L.x_off = take(size_t(kMaxR) * d * 4);
-    L.q_off = take(size_t(kMaxR) * qd * 4);
-    L.att_off = take(size_t(kMaxR) * qd * 4);
-    L.act_off = take(size_t(kMaxR) * c->d_ffn * 4);
-    L.ss_groups = ceil_div(d, kGroupRows);
-    L.ss_off = take(size_t(L.ss_groups) * kMaxR * 4);
-    size_t part_floats = 0;
-    int32_t counters = 0;
-    const GemmPlan* plans[4] = {&L.p_qkv, &L.p_wo, &L.p_gu, &L.p_wd};
-    for (const GemmPlan* p : plans) {
-        size_t f = size_t(p->groups) * p->splits * kGroupRows * kMaxR;
-        if (p->splits > 1 && f > part_floats) part_floats = f;
-        if (p->groups > counters) counters = p->groups;
-    }
-    L.part_off = take(part_floats * 4);
-    L.n_counters = counters;
-    L.cnt_off = take(size_t(counters) * 4);
-    // attention partials: per (kv head, row-tile pair, split): M[32], L[32], O[32][h]
     const int32_t G = c->n_q_heads / c->n_kv_heads;
-    L.attn_row_tiles_max = ceil_div(G * kMaxR, 16);
-    const int32_t pairs = ceil_div(L.attn_row_tiles_max, 2);
-    L.attn_max_splits = 64;
-    L.apart_off = take(size_t(c->n_kv_heads) * pairs * L.attn_max_splits * 32 * (h + 2) * 4);
-    L.acnt_off = take(size_t(c->n_kv_heads) * pairs * 4);
-    L.best_off = take(size_t(kMaxR) * 8);
-    L.rope_off = take(size_t(kMaxR) * h * 4);  // cos[32][h/2] then sin[32][h/2]
     // persistent kernel: one copy of every hand-over buffer per layer and phase
     auto frag_elems = [](int32_t K) { return size_t(ceil_div(K, kTileK)) * 4 * kMaxR * 16; };
     const int32_t versions = 2 * c->n_layers + 1;

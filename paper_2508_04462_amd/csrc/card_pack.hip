@@ -1,0 +1,68 @@
+// Weight re-layout (canonical row-major -> matrix-instruction tile order) and the KV read-back helper.
+#pragma once
+#include "card_common.hip"
+
+namespace card {
+
+// ------------------------------------------------------------------------------------------
+// Weight re-layout: canonical row-major bf16 -> tile order.  One thread per 8-element chunk.
+// ------------------------------------------------------------------------------------------
+enum RowMap { MAP_IDENT = 0, MAP_ROPE = 1, MAP_GATE = 2, MAP_UP = 3 };
+
+struct PackArgs {
+    const __bf16* src;  // [src_rows][K]
+    __bf16* dst;        // packed matrix base
+    int32_t src_rows, K, Ks, n_rows;  // n_rows: packed rows this call fills (incl. zero padding)
+    int32_t prow0;      // first packed row (MAP_IDENT / MAP_ROPE)
+    int32_t map, head_dim;
+};
+
+__global__ __launch_bounds__(256) void k_pack(PackArgs a) {
+    const int64_t chunks_per_row = int64_t(a.Ks) * 4;
+    const int64_t id = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (id >= int64_t(a.n_rows) * chunks_per_row) return;
+    const int idx = int(id / chunks_per_row), ch = int(id % chunks_per_row);
+    int prow, srow;
+    if (a.map == MAP_IDENT) {
+        prow = a.prow0 + idx;
+        srow = idx;
+    } else if (a.map == MAP_ROPE) {
+        prow = a.prow0 + idx;
+        const int h = a.head_dim, i = idx % h;
+        srow = (idx / h) * h + (i >> 1) + (i & 1) * (h >> 1);
+    } else {
+        prow = (idx >> 3) * 16 + (idx & 7) + (a.map == MAP_UP ? 8 : 0);
+        srow = idx;
+    }
+    const int k0 = ch * 8;
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = static_cast<__bf16>(0.f);
+    if (srow < a.src_rows && k0 < a.K) v = *reinterpret_cast<const bf16x8*>(a.src + size_t(srow) * a.K + k0);
+    const int t = prow >> 4, s = ch >> 2;
+    const int lane = (ch & 3) * 16 + (prow & 15);
+    reinterpret_cast<bf16x8*>(a.dst)[(size_t(t) * a.Ks + s) * 64 + lane] = v;
+}
+
+struct GatherArgs {
+    const __bf16* kpool;
+    const __bf16* vpool;
+    const int32_t* block_table;
+    int32_t first, count, n_kv_heads, head_dim;
+    float* k_out;
+    float* v_out;
+};
+
+__global__ __launch_bounds__(256) void k_kv_gather(GatherArgs a) {
+    const int64_t id = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const int h = a.head_dim;
+    if (id >= int64_t(a.count) * a.n_kv_heads * h) return;
+    const int j = int(id % h), head = int((id / h) % a.n_kv_heads), i = int(id / (int64_t(h) * a.n_kv_heads));
+    const int slot = a.first + i;
+    const int page = a.block_table[slot >> 4], tk = slot & 15;
+    const size_t base = (size_t(page) * a.n_kv_heads + head) * (16 * h);
+    a.k_out[id] = static_cast<float>(a.kpool[base + ((j >> 3) * 16 + tk) * 8 + (j & 7)]);
+    a.v_out[id] = static_cast<float>(a.vpool[base + v_page_index(j, tk)]);
+}
+
+}  // namespace card

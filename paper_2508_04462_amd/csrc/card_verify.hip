@@ -22,13 +22,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "card_kernels.hip"
-#include "card_layout.h"
+#include "card_common.hip"
 
 namespace card {
 
-typedef __attribute__((ext_vector_type(4))) unsigned int uint4v;
-typedef const __attribute__((address_space(1))) void* gptr_t;
+
+typedef __attribute__((ext_vector_type(2))) unsigned int uint2v;
 
 constexpr int kMegaWaves = 4;             // one wavefront per SIMD: each may use all 512 vector registers
 constexpr int kMegaThreads = kMegaWaves * 64;
@@ -587,24 +586,26 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                     const int slot = a.ctx_len + m2;
                     const int page = a.block_table[slot >> 4], tk = slot & 15;
                     const int run = min(r - m2, 16 - tk);
-                    const size_t vo = (size_t(page) * a.Hkv + head) * (16 * h) + jg * 16 + tk;
+                    const size_t vb = (size_t(page) * a.Hkv + head) * (16 * h);
+                    auto val = [&](int t) {
+                        return static_cast<__bf16>(sm.tile[(i * 16 + jj) * COLS + m2 + t] * sm.row_scale[m2 + t]);
+                    };
                     int q = 0;
-                    while (q < run) {
-                        auto val = [&](int t) {
-                            return static_cast<__bf16>(sm.tile[(i * 16 + jj) * COLS + m2 + t] * sm.row_scale[m2 + t]);
-                        };
-                        if (((tk + q) & 7) == 0 && q + 8 <= run) {
-                            uint4v w;
-#pragma unroll
-                            for (int e = 0; e < 8; e += 2) w[e / 2] = pack_bf16(val(q + e), val(q + e + 1));
-                            st_dev_b128(ea.vpool, uint32_t((vo + q) * 2), w);
-                            q += 8;
-                        } else if (((tk + q) & 1) == 0 && q + 2 <= run) {
-                            __hip_atomic_store(reinterpret_cast<uint32_t*>(ea.vpool + vo + q), pack_bf16(val(q), val(q + 1)),
+                    while (q < run) {  // four consecutive aligned tokens are 8 contiguous bytes
+                        const int t = tk + q;
+                        __bf16* dst = ea.vpool + vb + v_page_index(jg, t);
+                        if ((t & 3) == 0 && q + 4 <= run) {
+                            const unsigned long long w = uint64_t(pack_bf16(val(q), val(q + 1))) |
+                                                         (uint64_t(pack_bf16(val(q + 2), val(q + 3))) << 32);
+                            __hip_atomic_store(reinterpret_cast<unsigned long long*>(dst), w, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                            q += 4;
+                        } else if ((t & 1) == 0 && q + 2 <= run) {
+                            __hip_atomic_store(reinterpret_cast<uint32_t*>(dst), pack_bf16(val(q), val(q + 1)),
                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             q += 2;
                         } else {
-                            st_dev_bf16(ea.vpool + vo + q, val(q));
+                            st_dev_bf16(dst, val(q));
                             q += 1;
                         }
                     }
@@ -649,16 +650,18 @@ __device__ __forceinline__ AttnTask attn_task(const MegaArgs& a, int task) {
 
 template <int H>
 __device__ __forceinline__ void attn_load_page(const MegaArgs& a, const __bf16* kpool, const __bf16* vpool, int kvh,
-                                               int pg, int lane, bf16x8 (&kf)[H / 32], short4v (&vf)[H / 16]) {
-    const int col = lane & 15, kq = lane >> 4;
-    const int pid = a.block_table[pg];
+                                               int pid, int lane, bf16x8 (&kf)[H / 32], short4v (&vf)[H / 16]) {
     const size_t base = (size_t(pid) * a.Hkv + kvh) * (16 * H);
     const bf16x8* kp = reinterpret_cast<const bf16x8*>(kpool + base) + lane;
-    const short4v* vp = reinterpret_cast<const short4v*>(vpool + base) + (col * 4 + kq);
+    const uint4v* vp = reinterpret_cast<const uint4v*>(vpool + base) + lane;
 #pragma unroll
     for (int st = 0; st < H / 32; ++st) kf[st] = kp[st * 64];
 #pragma unroll
-    for (int i = 0; i < H / 16; ++i) vf[i] = vp[i * 64];
+    for (int i = 0; i < H / 32; ++i) {  // one 16-byte load = the operands of two 16-row tiles
+        const uint4v w = vp[i * 64];
+        vf[2 * i] = __builtin_bit_cast(short4v, uint2v{w[0], w[1]});
+        vf[2 * i + 1] = __builtin_bit_cast(short4v, uint2v{w[2], w[3]});
+    }
 }
 
 // Second half of an attention task, kept out of line so that its index arithmetic does not
@@ -666,7 +669,7 @@ __device__ __forceinline__ void attn_load_page(const MegaArgs& a, const __bf16* 
 // either finish (context not cut) or hand the cut's partial over and let the last workgroup of
 // this (kv head, row tile) merge all cuts.
 template <int H>
-__device__ __attribute__((noinline)) void attn_finish(MegaSmem& sm, float* apart, uint32_t* acount, __bf16* attfrag_l,
+__device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t* acount, __bf16* attfrag_l,
                                                       int G, int rp, int R, int a_splits, int row_tiles, int task,
                                                       int split, int kvh, int rt) {
     constexpr int PART = 16 * (H + 2);
@@ -787,7 +790,7 @@ __device__ __attribute__((noinline)) void attn_finish(MegaSmem& sm, float* apart
 // register file allows next to the query and output tiles.
 template <int H>
 struct AttnBufs {
-    static constexpr int N = H == 128 ? 3 : 4;
+    static constexpr int N = H == 128 ? 6 : 8;
     bf16x8 k[N][H / 32];
     short4v v[N][H / 16];
 };
@@ -796,27 +799,31 @@ struct AttnBufs {
 // context only (they do not depend on this layer's QKV phase).  loaded[i] tells the phase.
 template <int H>
 __device__ __forceinline__ void attn_preload(const MegaArgs& a, int layer, int wave, int lane, int wg, AttnBufs<H>& bf,
-                                             bool (&loaded)[4]) {
+                                             bool (&loaded)[8]) {
     constexpr int NBUF = AttnBufs<H>::N;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) loaded[i] = false;
+    for (int i = 0; i < NBUF; ++i) loaded[i] = false;
     if (wg >= a.Hkv * a.row_tiles * a.a_splits) return;
     const AttnTask t = attn_task(a, wg);
     const __bf16* kpool = a.kpool + size_t(layer) * a.pool_layer_elems;
     const __bf16* vpool = a.vpool + size_t(layer) * a.pool_layer_elems;
+    // page ids first, page loads after: loads complete in issue order, so a page id fetched
+    // between two page loads would wait for the whole page in front of it
+    int pid[NBUF];
 #pragma unroll
     for (int i = 0; i < NBUF; ++i) {
         const int pg = t.pg0 + wave + i * kMegaWaves;
-        if (pg < t.pg1 && (pg + 1) * 16 <= a.ctx_len) {
-            attn_load_page<H>(a, kpool, vpool, t.kvh, pg, lane, bf.k[i], bf.v[i]);
-            loaded[i] = true;
-        }
+        loaded[i] = pg < t.pg1 && (pg + 1) * 16 <= a.ctx_len;
+        pid[i] = loaded[i] ? a.block_table[pg] : 0;
     }
+#pragma unroll
+    for (int i = 0; i < NBUF; ++i)
+        if (loaded[i]) attn_load_page<H>(a, kpool, vpool, t.kvh, pid[i], lane, bf.k[i], bf.v[i]);
 }
 
 template <int H>
 __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSmem& sm, int wave, int lane, int wg,
-                                           AttnBufs<H>& bf, bool (&loaded)[4]) {
+                                           AttnBufs<H>& bf, bool (&loaded)[8]) {
     constexpr int ST = H / 32, HT = H / 16, PART = 16 * (H + 2), NBUF = AttnBufs<H>::N;
     const int tid = threadIdx.x;
     const int R = a.G * a.r;
@@ -832,12 +839,21 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
         const int mrow = row_ok ? rho / a.G : -1;
         const int limit = a.ctx_len + mrow;  // last visible position of this lane's row
         int pg = t.pg0 + wave;
+        {
+            int pid[NBUF];
+            bool need[NBUF];
 #pragma unroll
-        for (int i = 0; i < NBUF; ++i) {
-            const int pgi = pg + i * kMegaWaves;
-            if (pgi < t.pg1 && !(task == wg && loaded[i]))
-                attn_load_page<H>(a, kpool, vpool, kvh, pgi, lane, bf.k[i], bf.v[i]);
+            for (int i = 0; i < NBUF; ++i) {
+                const int pgi = pg + i * kMegaWaves;
+                need[i] = pgi < t.pg1 && !(task == wg && loaded[i]);
+                pid[i] = need[i] ? a.block_table[pgi] : 0;
+            }
+#pragma unroll
+            for (int i = 0; i < NBUF; ++i)
+                if (need[i]) attn_load_page<H>(a, kpool, vpool, kvh, pid[i], lane, bf.k[i], bf.v[i]);
         }
+        // page id of the page that will refill the buffer in use (one rotation ahead)
+        int pid_next = (pg + NBUF * kMegaWaves < t.pg1) ? a.block_table[pg + NBUF * kMegaWaves] : 0;
         bf16x8 qh[ST], ql[ST];
         {
             const bf16x8* qp = reinterpret_cast<const bf16x8*>(
@@ -906,7 +922,11 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
                 if (pg < t.pg1) {
                     use_page(pg, bf.k[i], bf.v[i]);
                     const int nx = pg + NBUF * kMegaWaves;
-                    if (nx < t.pg1) attn_load_page<H>(a, kpool, vpool, kvh, nx, lane, bf.k[i], bf.v[i]);
+                    if (nx < t.pg1) attn_load_page<H>(a, kpool, vpool, kvh, pid_next, lane, bf.k[i], bf.v[i]);
+                    // fetch the id for the following refill now: it is issued behind the page loads
+                    // and will have arrived one page later
+                    const int nx2 = nx + kMegaWaves;
+                    pid_next = nx2 < t.pg1 ? a.block_table[nx2] : 0;
                 }
                 pg += kMegaWaves;
             }
@@ -936,7 +956,7 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
 // of pushing the streaming loops into spills.  Arguments come straight from the kernel-argument
 // segment.  Returns the barrier generation.
 template <int H>
-__device__ __attribute__((noinline)) uint32_t attention_block(const MegaArgs* ap, int l, MegaSmem* smp, uint32_t gen) {
+__device__ __forceinline__ uint32_t attention_block(const MegaArgs* ap, int l, MegaSmem* smp, uint32_t gen) {
     const MegaArgs& a = *ap;
     MegaSmem& sm = *smp;
     const int tid = threadIdx.x;
@@ -944,11 +964,14 @@ __device__ __attribute__((noinline)) uint32_t attention_block(const MegaArgs* ap
     const int wg = blockIdx.x;
     const bool tsl = a.ts && l == a.ts_layer && tid == 0;
     if (tsl) a.ts[size_t(wg) * 32 + 16] = wall_clock64();
-    store_wait<0>();  // the QKV phase's stores (queries, new K and V rows)
-    if (tsl) a.ts[size_t(wg) * 32 + 11] = wall_clock64();
+    // page loads of old context first, then wait for everything issued so far: the QKV phase's
+    // stores (queries, new K and V rows) must be acknowledged before the barrier, and the pages
+    // are needed right after it anyway
     AttnBufs<H> bf;
-    bool loaded[4];
+    bool loaded[8];
     attn_preload<H>(a, l, wave, lane, wg, bf, loaded);
+    if (tsl) a.ts[size_t(wg) * 32 + 11] = wall_clock64();
+    store_wait<0>();
     if (tsl) a.ts[size_t(wg) * 32 + 12] = wall_clock64();
     grid_wait(a, gen, sm);
     if (tsl) a.ts[size_t(wg) * 32 + 2] = wall_clock64();
