@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--r", type=int, default=None)
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: a 1 GiB device copy (calibration) and 5 verify steps, no timing")
     return ap.parse_args()
 
 
@@ -138,6 +140,17 @@ def main():
         st = tgt.enqueue_verify(ctx, g0, r, cand=cand_dev[i % (r + 1)])
         if st != card.CARD_OK:
             raise card.CardError(st, "card_verify")
+
+    if args.pmc_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        for i in range(5):
+            step(i)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": True, "copy_bytes": 1 << 30, "verify_steps": 5}))
+        return
 
     for i in range(args.warmup):
         step(i)
