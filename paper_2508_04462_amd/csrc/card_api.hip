@@ -93,7 +93,7 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.eps = cfg->rms_eps;
     a.inv_d = 1.0f / float(cfg->d_model);
     a.theta = cfg->rope_theta;
-    a.inv_sqrt_h = 1.0f / sqrtf(float(h));
+    a.inv_sqrt_h = 1.4426950408889634f / sqrtf(float(h));  // log2(e)/sqrt(h): the softmax runs on exp2
     a.wbase = static_cast<const char*>(packed);
     a.embed_off = L.embed_off;
     a.g_final_off = L.g_final_off;

@@ -31,7 +31,7 @@ typedef __attribute__((ext_vector_type(2))) unsigned int uint2v;
 
 constexpr int kMegaWaves = 4;             // one wavefront per SIMD: each may use all 512 vector registers
 constexpr int kMegaThreads = kMegaWaves * 64;
-constexpr int kRing = 32;                 // weight fragments (1 KiB each) in flight per wavefront
+constexpr int kRing = 16;                 // weight fragments (1 KiB each) in flight per wavefront
 constexpr uint32_t kSpinLimit = 1u << 20; // bounded barrier wait: the kernel always terminates
 
 struct MegaArgs {
@@ -679,7 +679,7 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
             for (int w = 0; w < kMegaWaves; ++w) mg = fmaxf(mg, sm.attn[w * PART + tid]);
             float l = 0.f;
             for (int w = 0; w < kMegaWaves; ++w) {
-                const float f = expf(sm.attn[w * PART + tid] - mg);
+                const float f = __builtin_amdgcn_exp2f(sm.attn[w * PART + tid] - mg);
                 sm.wgt[w * 16 + tid] = f;
                 l += f * sm.attn[w * PART + 16 + tid];
             }
@@ -741,7 +741,7 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
                     for (int sp = 0; sp < S; ++sp) mg = fmaxf(mg, ml[sp * 16 + tid]);
                     float l = 0.f;
                     for (int sp = 0; sp < S; ++sp) {
-                        const float f = expf(ml[sp * 16 + tid] - mg);
+                        const float f = __builtin_amdgcn_exp2f(ml[sp * 16 + tid] - mg);
                         wl[sp * 16 + tid] = f;
                         l += f * ml[512 + sp * 16 + tid];
                     }
@@ -852,8 +852,6 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
             for (int i = 0; i < NBUF; ++i)
                 if (need[i]) attn_load_page<H>(a, kpool, vpool, kvh, pid[i], lane, bf.k[i], bf.v[i]);
         }
-        // page id of the page that will refill the buffer in use (one rotation ahead)
-        int pid_next = (pg + NBUF * kMegaWaves < t.pg1) ? a.block_table[pg + NBUF * kMegaWaves] : 0;
         bf16x8 qh[ST], ql[ST];
         {
             const bf16x8* qp = reinterpret_cast<const bf16x8*>(
@@ -869,66 +867,92 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
         for (int i = 0; i < HT; ++i) o[i] = floatx4{0.f, 0.f, 0.f, 0.f};
         float mx = -1e30f, sum = 0.f;
 
-        auto use_page = [&](int pgi, const bf16x8 (&kf)[ST], const short4v (&vf)[HT]) {
-            floatx4 sc = floatx4{0.f, 0.f, 0.f, 0.f};
+        // Two pages per round: one max / sum reduction across the lane groups and one rescale of
+        // the output tile serve 32 keys.  Scores are in log2 units (the query carries log2(e)/sqrt(h)).
+        auto use_two = [&](int pga, const bf16x8 (&ka)[ST], const short4v (&va)[HT], int pgb, const bf16x8 (&kb)[ST],
+                           const short4v (&vb)[HT]) {
+            floatx4 sa = floatx4{0.f, 0.f, 0.f, 0.f}, sb = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
-                sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[st], qh[st], sc, 0, 0, 0);
-                sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[st], ql[st], sc, 0, 0, 0);
+                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[st], qh[st], sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[st], qh[st], sb, 0, 0, 0);
+                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[st], ql[st], sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[st], ql[st], sb, 0, 0, 0);
             }
             float pmax = -1e30f;
-            bool ok[4];
+            bool oka[4], okb[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                ok[v] = mrow >= 0 && (pgi * 16 + kq * 4 + v) <= limit;
-                if (ok[v]) pmax = fmaxf(pmax, sc[v]);
+                oka[v] = mrow >= 0 && (pga * 16 + kq * 4 + v) <= limit;
+                okb[v] = mrow >= 0 && pgb < t.pg1 && (pgb * 16 + kq * 4 + v) <= limit;
+                if (oka[v]) pmax = fmaxf(pmax, sa[v]);
+                if (okb[v]) pmax = fmaxf(pmax, sb[v]);
             }
             pmax = fmaxf(pmax, __shfl_xor(pmax, 16));
             pmax = fmaxf(pmax, __shfl_xor(pmax, 32));
             const float mnew = fmaxf(mx, pmax);
-            const float alpha = expf(mx - mnew);
-            float pr[4], psum = 0.f;
+            const float alpha = __builtin_amdgcn_exp2f(mx - mnew);
+            float pa[4], pb[4], psum = 0.f;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                pr[v] = ok[v] ? expf(sc[v] - mnew) : 0.f;
-                psum += pr[v];
+                pa[v] = oka[v] ? __builtin_amdgcn_exp2f(sa[v] - mnew) : 0.f;
+                pb[v] = okb[v] ? __builtin_amdgcn_exp2f(sb[v] - mnew) : 0.f;
+                psum += pa[v] + pb[v];
             }
             psum += __shfl_xor(psum, 16);
             psum += __shfl_xor(psum, 32);
             sum = sum * alpha + psum;
             mx = mnew;
-            short4v ph, pl;
+            short4v pah, pal, pbh, pbl;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 __bf16 hi, lo;
-                split_bf16(pr[v], hi, lo);
-                ph[v] = __builtin_bit_cast(short, hi);
-                pl[v] = __builtin_bit_cast(short, lo);
+                split_bf16(pa[v], hi, lo);
+                pah[v] = __builtin_bit_cast(short, hi);
+                pal[v] = __builtin_bit_cast(short, lo);
+                split_bf16(pb[v], hi, lo);
+                pbh[v] = __builtin_bit_cast(short, hi);
+                pbl[v] = __builtin_bit_cast(short, lo);
             }
 #pragma unroll
             for (int i = 0; i < HT; ++i) {
                 floatx4 acc = o[i];
                 acc[0] *= alpha; acc[1] *= alpha; acc[2] *= alpha; acc[3] *= alpha;
-                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[i], ph, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[i], pl, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[i], pah, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb[i], pbh, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[i], pal, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb[i], pbl, acc, 0, 0, 0);
                 o[i] = acc;
             }
         };
         if (a.ts && layer == a.ts_layer && tid == 0) a.ts[size_t(wg) * 32 + 13] = wall_clock64();
-        // buffers in rotation: NBUF - 1 pages stay in flight behind the one in use
+        // buffers in rotation, two at a time: the others stay in flight behind the pair in use
+        static_assert(NBUF % 2 == 0, "pairs");
+        int pid_nx[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int nx = pg + (NBUF + q) * kMegaWaves;
+            pid_nx[q] = nx < t.pg1 ? a.block_table[nx] : 0;
+        }
         while (pg < t.pg1) {
 #pragma unroll
-            for (int i = 0; i < NBUF; ++i) {
+            for (int i = 0; i < NBUF; i += 2) {
                 if (pg < t.pg1) {
-                    use_page(pg, bf.k[i], bf.v[i]);
-                    const int nx = pg + NBUF * kMegaWaves;
-                    if (nx < t.pg1) attn_load_page<H>(a, kpool, vpool, kvh, pid_next, lane, bf.k[i], bf.v[i]);
-                    // fetch the id for the following refill now: it is issued behind the page loads
-                    // and will have arrived one page later
-                    const int nx2 = nx + kMegaWaves;
-                    pid_next = nx2 < t.pg1 ? a.block_table[nx2] : 0;
+                    use_two(pg, bf.k[i], bf.v[i], pg + kMegaWaves, bf.k[i + 1], bf.v[i + 1]);
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const int nx = pg + (NBUF + q) * kMegaWaves;
+                        if (nx < t.pg1) attn_load_page<H>(a, kpool, vpool, kvh, pid_nx[q], lane, bf.k[i + q], bf.v[i + q]);
+                    }
+                    // ids for the refills after these: behind the page loads in the queue, they will
+                    // have arrived a round later
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const int nx2 = pg + (NBUF + 2 + q) * kMegaWaves;
+                        pid_nx[q] = nx2 < t.pg1 ? a.block_table[nx2] : 0;
+                    }
                 }
-                pg += kMegaWaves;
+                pg += 2 * kMegaWaves;
             }
         }
 
@@ -968,6 +992,14 @@ __device__ __forceinline__ uint32_t attention_block(const MegaArgs* ap, int l, M
     // stores (queries, new K and V rows) must be acknowledged before the barrier, and the pages
     // are needed right after it anyway
     AttnBufs<H> bf;
+    // a pair's second page may not exist: its probabilities are zero, its buffer must be finite
+#pragma unroll
+    for (int i = 0; i < AttnBufs<H>::N; ++i) {
+#pragma unroll
+        for (int q = 0; q < H / 32; ++q) bf.k[i][q] = __builtin_bit_cast(bf16x8, uint4v{0u, 0u, 0u, 0u});
+#pragma unroll
+        for (int q = 0; q < H / 16; ++q) bf.v[i][q] = short4v{0, 0, 0, 0};
+    }
     bool loaded[8];
     attn_preload<H>(a, l, wave, lane, wg, bf, loaded);
     if (tsl) a.ts[size_t(wg) * 32 + 11] = wall_clock64();
