@@ -790,7 +790,7 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
 // register file allows next to the query and output tiles.
 template <int H>
 struct AttnBufs {
-    static constexpr int N = H == 128 ? 6 : 8;
+    static constexpr int N = H == 128 ? 4 : 8;  // 8 loads per page and head at H = 128: at most ~32 loads in flight per wavefront pay off
     bf16x8 k[N][H / 32];
     short4v v[N][H / 16];
 };
@@ -799,7 +799,7 @@ struct AttnBufs {
 // context only (they do not depend on this layer's QKV phase).  loaded[i] tells the phase.
 template <int H>
 __device__ __forceinline__ void attn_preload(const MegaArgs& a, int layer, int wave, int lane, int wg, AttnBufs<H>& bf,
-                                             bool (&loaded)[8]) {
+                                             const int (&pid)[8], bool (&loaded)[8]) {
     constexpr int NBUF = AttnBufs<H>::N;
 #pragma unroll
     for (int i = 0; i < NBUF; ++i) loaded[i] = false;
@@ -807,23 +807,34 @@ __device__ __forceinline__ void attn_preload(const MegaArgs& a, int layer, int w
     const AttnTask t = attn_task(a, wg);
     const __bf16* kpool = a.kpool + size_t(layer) * a.pool_layer_elems;
     const __bf16* vpool = a.vpool + size_t(layer) * a.pool_layer_elems;
-    // page ids first, page loads after: loads complete in issue order, so a page id fetched
-    // between two page loads would wait for the whole page in front of it
-    int pid[NBUF];
 #pragma unroll
     for (int i = 0; i < NBUF; ++i) {
         const int pg = t.pg0 + wave + i * kMegaWaves;
         loaded[i] = pg < t.pg1 && (pg + 1) * 16 <= a.ctx_len;
-        pid[i] = loaded[i] ? a.block_table[pg] : 0;
-    }
-#pragma unroll
-    for (int i = 0; i < NBUF; ++i)
         if (loaded[i]) attn_load_page<H>(a, kpool, vpool, t.kvh, pid[i], lane, bf.k[i], bf.v[i]);
+    }
+}
+
+// The page ids of a workgroup's first attention task are the same in every layer (one block
+// table for all layers): fetched once at kernel start, so that no page load ever waits for an id
+// queued behind a phase's stores.
+template <int H>
+__device__ __forceinline__ void attn_page_ids(const MegaArgs& a, int wave, int wg, int (&pid)[8]) {
+    constexpr int NBUF = AttnBufs<H>::N;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pid[i] = 0;
+    if (wg >= a.Hkv * a.row_tiles * a.a_splits) return;
+    const AttnTask t = attn_task(a, wg);
+#pragma unroll
+    for (int i = 0; i < NBUF; ++i) {
+        const int pg = t.pg0 + wave + i * kMegaWaves;
+        if (pg < t.pg1) pid[i] = __builtin_amdgcn_readfirstlane(a.block_table[pg]);
+    }
 }
 
 template <int H>
 __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSmem& sm, int wave, int lane, int wg,
-                                           AttnBufs<H>& bf, bool (&loaded)[8]) {
+                                           AttnBufs<H>& bf, const int (&pid0)[8], bool (&loaded)[8]) {
     constexpr int ST = H / 32, HT = H / 16, PART = 16 * (H + 2), NBUF = AttnBufs<H>::N;
     const int tid = threadIdx.x;
     const int R = a.G * a.r;
@@ -846,7 +857,7 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
             for (int i = 0; i < NBUF; ++i) {
                 const int pgi = pg + i * kMegaWaves;
                 need[i] = pgi < t.pg1 && !(task == wg && loaded[i]);
-                pid[i] = need[i] ? a.block_table[pgi] : 0;
+                pid[i] = task == wg ? pid0[i] : (need[i] ? a.block_table[pgi] : 0);
             }
 #pragma unroll
             for (int i = 0; i < NBUF; ++i)
@@ -980,7 +991,8 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
 // of pushing the streaming loops into spills.  Arguments come straight from the kernel-argument
 // segment.  Returns the barrier generation.
 template <int H>
-__device__ __forceinline__ uint32_t attention_block(const MegaArgs* ap, int l, MegaSmem* smp, uint32_t gen) {
+__device__ __forceinline__ uint32_t attention_block(const MegaArgs* ap, int l, MegaSmem* smp, uint32_t gen,
+                                                   const int (&pid0)[8]) {
     const MegaArgs& a = *ap;
     MegaSmem& sm = *smp;
     const int tid = threadIdx.x;
@@ -1001,13 +1013,13 @@ __device__ __forceinline__ uint32_t attention_block(const MegaArgs* ap, int l, M
         for (int q = 0; q < H / 16; ++q) bf.v[i][q] = short4v{0, 0, 0, 0};
     }
     bool loaded[8];
-    attn_preload<H>(a, l, wave, lane, wg, bf, loaded);
+    attn_preload<H>(a, l, wave, lane, wg, bf, pid0, loaded);
     if (tsl) a.ts[size_t(wg) * 32 + 11] = wall_clock64();
     store_wait<0>();
     if (tsl) a.ts[size_t(wg) * 32 + 12] = wall_clock64();
     grid_wait(a, gen, sm);
     if (tsl) a.ts[size_t(wg) * 32 + 2] = wall_clock64();
-    attn_phase<H>(a, l, sm, wave, lane, wg, bf, loaded);
+    attn_phase<H>(a, l, sm, wave, lane, wg, bf, pid0, loaded);
     return gen;
 }
 
@@ -1077,6 +1089,8 @@ __global__ __launch_bounds__(kMegaThreads) __attribute__((amdgpu_waves_per_eu(1,
     store_wait<0>();  // the embed stores are younger than the first ring fill
     grid_wait(a, gen, sm);
 
+    int pid0[8];
+    attn_page_ids<H>(a, wave, wg, pid0);
     const size_t xres_stride = size_t(kMaxR) * a.d, ss_stride = size_t(n_dt) * kMaxR;
     // end of a GEMM phase whose ring runs ahead into `nx`: wait for the stores only, cross the
     // barrier, then let the polling wavefront catch up on the half of the ring it held back
@@ -1107,7 +1121,7 @@ __global__ __launch_bounds__(kMegaThreads) __attribute__((amdgpu_waves_per_eu(1,
         gemm_phase<NB_QKV, MT, ME_QKV, false>(a, p_qkv, a.xfrag + v0 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea,
                                               ring, first_src<NB_ONE>(p_wo, nwg), sm, wave, lane);
         CARD_TS(1)
-        gen = attention_block<H>((const MegaArgs*)__builtin_amdgcn_kernarg_segment_ptr(), l, &sm, gen);
+        gen = attention_block<H>((const MegaArgs*)__builtin_amdgcn_kernarg_segment_ptr(), l, &sm, gen, pid0);
         // the ring was empty during attention; start it on the O-projection behind the stores
         // (the wavefront that polls the barrier fills its ring only after the barrier)
         if (wave != 0) ring_fill(ring, first_src<NB_ONE>(p_wo, nwg), lane);
