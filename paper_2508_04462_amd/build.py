@@ -26,7 +26,7 @@ def build_library(verbose: bool = False) -> str:
         "-I", os.path.join(ROOT, "include"),
         "-I", os.path.join(PKG_DIR, "csrc"),
         "-o", LIB_PATH,
-    ] + SOURCES
+    ] + os.environ.get("CARD_EXTRA_FLAGS", "").split() + SOURCES
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -1,4 +1,6 @@
 // C ABI of libcard: argument checks and the launch sequence of one verification step.
+#include <algorithm>
+#include <cstdlib>
 #include <hip/hip_runtime.h>
 
 #include <vector>
@@ -51,11 +53,17 @@ int cu_count() {
     return cus;
 }
 
+// Workgroups of the verify kernel: one per compute unit, at most 256 (the barrier polls 256 flags).
+int grid_size() {
+    const int cus = cu_count();
+    return cus > 256 ? 256 : cus;
+}
+
 template <int MT, int H>
 int launch_mega(MegaArgs& a, hipStream_t st) {
     void* params[] = {&a};
     const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<void*>(k_verify<MT, H>), dim3(a.nwg),
-                                                    dim3(kMegaThreads), params, 0, st);
+                                                    dim3(kBlockThreads), params, 0, st);
     return e == hipSuccess ? CARD_OK : CARD_EDEVICE;
 }
 
@@ -70,9 +78,8 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     if (r < 1 || r > cfg->max_r) return CARD_ERANGE;
     if (ctx_len < 0) return CARD_EINVAL;
     if (int64_t(ctx_len) + r > cfg->max_ctx) return CARD_ECAPACITY;
-    int cus = cu_count();
+    const int cus = grid_size();
     if (cus <= 0) return CARD_EDEVICE;
-    if (cus > 256) cus = 256;  // the barrier polls at most 256 flag words
 
     char* ws = static_cast<char*>(workspace);
     const int h = cfg->head_dim;
@@ -98,6 +105,7 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.embed_off = L.embed_off;
     a.g_final_off = L.g_final_off;
     a.layer0_off = L.layer0_off;
+    a.stamp = reinterpret_cast<const uint32_t*>(a.wbase + L.stamp_off);
     a.layer_stride = L.layer_stride;
     a.g_attn_off = L.g_attn_off;
     a.g_ffn_off = L.g_ffn_off;
@@ -112,9 +120,13 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.block_table = kv->block_table;
     a.pages_used = ceil_div(ctx_len + r, kKvBlock);
     a.row_tiles = ceil_div(a.G * r, 16);
-    // cut the context only when a wavefront would walk more than ten pages (pages are pulled into
-    // the near cache ahead of time, so a short walk is cheaper than merging cuts)
-    int splits = ceil_div(a.pages_used, 10 * kMegaWaves);
+    // Cut the context so that a workgroup's share fits the page buffers of its wavefronts (all of
+    // its old-context pages are then in flight before the barrier in front of attention), as long
+    // as every task still gets a workgroup of its own; beyond that the shares grow instead.
+    const int share = kMegaWaves * (h == 128 ? 2 : 4);
+    int splits = ceil_div(a.pages_used, share);
+    const int max_by_grid = std::max(1, cus / (a.Hkv * a.row_tiles));
+    if (splits > max_by_grid) splits = max_by_grid;
     if (splits > L.m_attn_max_splits) splits = L.m_attn_max_splits;
     a.pages_per_split = ceil_div(a.pages_used, splits);
     a.a_splits = ceil_div(a.pages_used, a.pages_per_split);
@@ -206,6 +218,14 @@ int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t 
         a.prow0 = prow0;
         a.map = map;
         a.head_dim = h;
+        a.Nt = m.Nt;
+        a.NB = m.NB;
+        a.nwg = grid_size();
+        if (a.nwg <= 0) return int(CARD_EDEVICE);
+        // whoever verifies with these weights must run the grid they were laid out for
+        if (hipMemsetD32Async(reinterpret_cast<hipDeviceptr_t>(pb + L.stamp_off), int(kStampMagic), 1, st) != hipSuccess ||
+            hipMemsetD32Async(reinterpret_cast<hipDeviceptr_t>(pb + L.stamp_off + 4), a.nwg, 1, st) != hipSuccess)
+            return int(CARD_EDEVICE);
         const int64_t total = int64_t(n_rows) * m.Ks * 4;
         hipLaunchKernelGGL(k_pack, dim3(uint32_t((total + 255) / 256)), dim3(256), 0, st, a);
         return launch_status();

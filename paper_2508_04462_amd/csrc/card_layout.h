@@ -12,19 +12,62 @@ constexpr int kTileN = 16;     // rows of one matrix-instruction tile (output fe
 constexpr int kTileK = 32;     // contraction depth of one bf16 16x16x32 matrix instruction
 constexpr int kMaxR = 32;
 constexpr int kKvBlock = 16;
+// tiles a workgroup accumulates side by side (batch width) per kind of matrix
+constexpr int kNbQkv = 2, kNbOne = 1, kNbWide = 8;
+constexpr uint32_t kStampMagic = 0x43415244u;  // "CARD"
 
-// One matrix in tile order: [Nt n-tiles][Ks k-steps][64 lanes][8 bf16]; lane l of tile (t, s)
-// holds row 16t + l%16, columns 32s + 8*(l/16) .. +8.  Rows / columns beyond N / K are zero.
+#ifdef __HIPCC__
+#define CARD_HD __host__ __device__
+#else
+#define CARD_HD
+#endif
+
+constexpr int kStreamWaves = 4;  // wavefront pairs of a workgroup: they cut the contraction four ways
+
+// One matrix as Nt n-tiles x Ks k-steps of 1 KiB fragments [64 lanes][8 bf16]: lane l of
+// fragment (t, s) holds row 16t + l%16, columns 32s + 8*(l/16) .. +8; rows / columns beyond
+// N / K are zero.  Fragments are stored in STREAM ORDER, the order in which the verify kernel
+// consumes them on a grid of nwg workgroups: tile t belongs to position p = t % nwg of the grid
+// (its j-th tile, j = t / nwg), k-step s to the wavefront pair w with w*Ks/4 <= s < (w+1)*Ks/4.
+// Memory holds position after position, inside a position pair after pair, and inside a pair
+// the tiles NB at a time ("batch"): batch, then k-step, then tile of the batch.  Every wavefront
+// pair therefore reads ONE contiguous run per matrix.
 struct MatDesc {
     size_t off;  // byte offset inside the packed blob (layer matrices: relative to the layer base)
-    int32_t N, K, Nt, Ks;
+    int32_t N, K, Nt, Ks, NB;
     size_t bytes() const { return size_t(Nt) * Ks * 1024; }
 };
+
+// Tiles of grid position p, the k-steps [s0, s1) of pair w, and the index of the pair's first
+// fragment in the matrix.
+struct StreamRun {
+    int32_t cnt, s0, s1;
+    int64_t first;
+};
+CARD_HD inline StreamRun stream_run(int32_t Nt, int32_t Ks, int32_t nwg, int32_t p, int32_t w) {
+    StreamRun r;
+    const int32_t full = Nt / nwg, rem = Nt % nwg;
+    r.cnt = full + (p < rem ? 1 : 0);
+    r.s0 = (w * Ks) / kStreamWaves;
+    r.s1 = ((w + 1) * Ks) / kStreamWaves;
+    r.first = (int64_t(full) * p + (p < rem ? p : rem)) * Ks + int64_t(r.cnt) * r.s0;
+    return r;
+}
+// Index of fragment (tile t, k-step s) in stream order.
+CARD_HD inline int64_t stream_frag_index(int32_t Nt, int32_t Ks, int32_t NB, int32_t nwg, int32_t t, int32_t s) {
+    const int32_t p = t % nwg, j = t / nwg;
+    int32_t w = 0;
+    while (w + 1 < kStreamWaves && s >= ((w + 1) * Ks) / kStreamWaves) ++w;
+    const StreamRun r = stream_run(Nt, Ks, nwg, p, w);
+    const int32_t b = j / NB, i = j % NB;
+    const int32_t nv = r.cnt - b * NB < NB ? r.cnt - b * NB : NB;
+    return r.first + int64_t(b) * NB * (r.s1 - r.s0) + int64_t(s - r.s0) * nv + i;
+}
 
 struct Layout {
     bool ok;
     // packed weights
-    size_t embed_off, lm_off, g_final_off, layer0_off, layer_stride, weight_bytes;
+    size_t embed_off, lm_off, g_final_off, stamp_off, layer0_off, layer_stride, weight_bytes;
     MatDesc qkv, wo, gu, wd, lm;  // layer matrices relative to the layer base; lm absolute
     size_t g_attn_off, g_ffn_off; // relative to the layer base
     size_t ws_bytes;
@@ -38,11 +81,12 @@ struct Layout {
 inline int32_t ceil_div(int64_t a, int64_t b) { return int32_t((a + b - 1) / b); }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-inline MatDesc make_mat(size_t off, int32_t N, int32_t K) {
+inline MatDesc make_mat(size_t off, int32_t N, int32_t K, int32_t NB) {
     MatDesc m;
     m.off = off;
     m.N = N;
     m.K = K;
+    m.NB = NB;
     m.Nt = ceil_div(N, kTileN);
     m.Ks = ceil_div(K, kTileK);
     return m;
@@ -70,20 +114,22 @@ inline Layout make_layout(const card_model_cfg* c) {
     size_t off = 0;
     L.embed_off = off;
     off = align_up(off + size_t(c->vocab) * d * 2, 1024);
-    L.lm = make_mat(off, c->vocab, d);
+    L.lm = make_mat(off, c->vocab, d, kNbWide);
     L.lm_off = off;
     off = align_up(off + L.lm.bytes(), 1024);
     L.g_final_off = off;
     off = align_up(off + size_t(d) * 4, 1024);
+    L.stamp_off = off;  // {magic, grid size the stream order was laid out for}
+    off += 1024;
     L.layer0_off = off;
     size_t lo = 0;
-    L.qkv = make_mat(lo, qd + 2 * kvd, d);
+    L.qkv = make_mat(lo, qd + 2 * kvd, d, kNbQkv);
     lo += L.qkv.bytes();
-    L.wo = make_mat(lo, d, qd);
+    L.wo = make_mat(lo, d, qd, kNbOne);
     lo += L.wo.bytes();
-    L.gu = make_mat(lo, 2 * c->d_ffn, d);
+    L.gu = make_mat(lo, 2 * c->d_ffn, d, kNbWide);
     lo += L.gu.bytes();
-    L.wd = make_mat(lo, d, c->d_ffn);
+    L.wd = make_mat(lo, d, c->d_ffn, kNbOne);
     lo += L.wd.bytes();
     L.g_attn_off = lo;
     lo = align_up(lo + size_t(d) * 4, 1024);

@@ -1,11 +1,11 @@
-// Weight re-layout (canonical row-major -> matrix-instruction tile order) and the KV read-back helper.
+// Weight re-layout (canonical row-major -> matrix-instruction fragments in stream order) and the KV read-back helper.
 #pragma once
 #include "card_common.hip"
 
 namespace card {
 
 // ------------------------------------------------------------------------------------------
-// Weight re-layout: canonical row-major bf16 -> tile order.  One thread per 8-element chunk.
+// Weight re-layout: canonical row-major bf16 -> fragments in stream order.  One thread per 8-element chunk.
 // ------------------------------------------------------------------------------------------
 enum RowMap { MAP_IDENT = 0, MAP_ROPE = 1, MAP_GATE = 2, MAP_UP = 3 };
 
@@ -13,6 +13,7 @@ struct PackArgs {
     const __bf16* src;  // [src_rows][K]
     __bf16* dst;        // packed matrix base
     int32_t src_rows, K, Ks, n_rows;  // n_rows: packed rows this call fills (incl. zero padding)
+    int32_t Nt, NB, nwg;              // stream order: tiles of the matrix, batch width, grid size
     int32_t prow0;      // first packed row (MAP_IDENT / MAP_ROPE)
     int32_t map, head_dim;
 };
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(256) void k_pack(PackArgs a) {
     if (srow < a.src_rows && k0 < a.K) v = *reinterpret_cast<const bf16x8*>(a.src + size_t(srow) * a.K + k0);
     const int t = prow >> 4, s = ch >> 2;
     const int lane = (ch & 3) * 16 + (prow & 15);
-    reinterpret_cast<bf16x8*>(a.dst)[(size_t(t) * a.Ks + s) * 64 + lane] = v;
+    reinterpret_cast<bf16x8*>(a.dst)[size_t(stream_frag_index(a.Nt, a.Ks, a.NB, a.nwg, t, s)) * 64 + lane] = v;
 }
 
 struct GatherArgs {

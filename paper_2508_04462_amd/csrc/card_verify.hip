@@ -1,17 +1,26 @@
 // The whole verification step as ONE persistent kernel (one workgroup per compute unit).
 //
-// Why: at r <= 32 rows a decoder layer is five dependent, HBM-bound phases of 4-30 us each;
-// launched as separate kernels the memory pipe drains at every boundary.  Here the phases are
-// separated by grid barriers instead, and - because weights never depend on activations - every
-// wavefront keeps a 16-fragment (16 KiB) register ring of weight tiles in flight that simply runs
-// ahead across the barrier into the next phase's weights.  HBM keeps streaming while the barrier
-// and the hand-over of the (tiny) activations take place.
+// Why: at r <= 32 rows a decoder layer is five dependent, HBM-bound phases of 4-30 us each,
+// separated by hand-overs of (tiny) activations that cost several microseconds of pure latency
+// each (store acknowledgement, barrier, first touch of the new activations).  Weights never
+// depend on activations, so the kernel decouples the two:
+//
+//   * four PRODUCER wavefronts per workgroup (one per SIMD) walk the workgroup's weight
+//     fragments of the whole step in consumption order, keep 8 loads of 1 KiB in flight each
+//     and push what arrives into a per-wavefront FIFO in LDS (28 KiB each).  The weights are
+//     stored in exactly that order, so each producer reads one contiguous run per matrix;
+//   * four CONSUMER wavefronts pop fragments from their FIFO into the matrix pipe, run the
+//     epilogues, the attention phase and the grid barriers.
+//
+// The producers never wait for a barrier, only for FIFO space: HBM keeps streaming through
+// every hand-over until 36 KiB per wavefront pair (37 MB on the whole part) are buffered, and
+// the consumers catch up from LDS afterwards.
 //
 // Hand-over rules (the part has one L2 per compute die, not coherent with the others):
 //   * everything one workgroup writes for another is stored with device scope (write-through);
 //   * every such buffer is written exactly once per call, at an address nobody has read before
 //     in this call (one copy per layer and phase), so plain cached loads can never hit a stale
-//     line; the barrier counter itself is only touched with device-scope atomics.
+//     line; the barrier flags themselves are only touched with device-scope accesses.
 //
 // Activations travel between phases already split into bf16 high + low halves and laid out in
 // the operand order of the matrix instruction ("fragment order"): element (row m, column k) of
@@ -29,15 +38,22 @@ namespace card {
 
 typedef __attribute__((ext_vector_type(2))) unsigned int uint2v;
 
-constexpr int kMegaWaves = 4;             // one wavefront per SIMD: each may use all 512 vector registers
+constexpr int kMegaWaves = 4;             // consumer wavefronts, one per SIMD (they cut K four ways)
 constexpr int kMegaThreads = kMegaWaves * 64;
-constexpr int kRing = 16;                 // weight fragments (1 KiB each) in flight per wavefront
+static_assert(kMegaWaves == kStreamWaves, "the weight layout assumes this many wavefront pairs");
+constexpr int kProdWaves = kMegaWaves;    // producer wavefront p feeds consumer wavefront p
+constexpr int kBlockThreads = (kMegaWaves + kProdWaves) * 64;
+constexpr int kRing = 8;                 // weight fragments (1 KiB each) in flight per producer
+constexpr int kFifo = 28;                 // fragment slots per FIFO
+constexpr int kGroup = 8;                 // fragments a consumer pops at a time (SG k-steps x NB tiles)
 constexpr uint32_t kSpinLimit = 1u << 20; // bounded barrier wait: the kernel always terminates
+constexpr uint32_t kLdsSpinLimit = 1u << 24;  // bounded FIFO waits (each poll is an LDS round trip)
 
 struct MegaArgs {
     int32_t L, d, qd, kvd, h, Hkv, G, F, V, r, rp, ctx_len, nwg;
     float eps, inv_d, theta, inv_sqrt_h;
     const char* wbase;
+    const uint32_t* stamp;  // {magic, grid size} the weights were laid out for
     size_t embed_off, g_final_off, layer0_off, layer_stride, g_attn_off, g_ffn_off;
     MatDesc qkv, wo, gu, wd, lm;  // lm.off absolute, the others relative to the layer base
     __bf16* kpool;
@@ -69,6 +85,7 @@ struct MegaArgs {
 };
 
 struct __align__(16) MegaSmem {
+    uint4v fifo[kMegaWaves][kFifo][64];               // weight fragments, producer -> consumer
     union {
         float red[kMegaWaves * 8 * 256];              // GEMM: per-wavefront accumulators (after the k-loop)
         float attn[kMegaWaves * 16 * (128 + 2)];      // attention: per-wavefront (M, L, O)
@@ -78,8 +95,13 @@ struct __align__(16) MegaSmem {
     float wgt[(kMegaWaves + 3) * 16];
     unsigned long long part_best[512];
     unsigned long long wg_best[kMaxR];
+    uint4v dump[64];             // where a producer writes ring slots that hold no fragment (end of the stream)
+    uint32_t tail[kMegaWaves];   // fragments pushed so far (written by the producer)
+    uint32_t head[kMegaWaves];   // fragments popped so far (written by the consumer)
+    uint32_t cbar;               // arrivals at the consumer barrier (monotonic)
     int failed;
     uint32_t epoch;
+    int pred[kMaxR + 1];
 };
 
 // ---- device-scope (write-through) stores -------------------------------------------------
@@ -129,26 +151,49 @@ __device__ __forceinline__ int opaque_v(int v) {
     return v;
 }
 
-// ---- grid barrier --------------------------------------------------------------------------
-// Stores and loads share one in-order counter on this part.  store_wait<PENDING> returns when
-// all of this thread's stores are acknowledged, given that exactly PENDING loads were issued
-// after the last store (the weight ring's run-ahead) and may stay in flight.
-template <int PENDING>
+// ---- waits and barriers ------------------------------------------------------------------------
+// All of this thread's global stores acknowledged.  (Consumer wavefronts have no long-latency
+// loads queued: the weight stream belongs to the producers.)
 __device__ __forceinline__ void store_wait() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    // s_waitcnt vmcnt(PENDING): vmcnt[3:0] | expcnt(7) << 4 | lgkmcnt(15) << 8 | vmcnt[5:4] << 14
-    __builtin_amdgcn_s_waitcnt((PENDING & 15) | (7 << 4) | (15 << 8) | ((PENDING >> 4) << 14));
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));  // vmcnt(0)
 }
 
-// Arrive and wait.  A single counter would serialise one device-scope atomic per workgroup
-// (about 10 us for 256 of them under load); instead every workgroup publishes the barrier's
-// sequence number in its own flag word and wavefront 0 of every workgroup polls all flags with
-// one 1 KiB device-scope load.  Sequence numbers keep growing across calls (`epoch`), so flags
-// never need clearing.  Loads complete in issue order per wavefront, so callers keep wavefront
-// 0's queue free of long-latency loads when it gets here.
-__device__ __forceinline__ void grid_wait(const MegaArgs& a, uint32_t& gen, MegaSmem& sm) {
-    __syncthreads();
+// lgkmcnt(0) only: vmcnt(63) expcnt(7)
+constexpr int kWaitLds = (63 & 15) | (7 << 4) | (0 << 8) | ((63 >> 4) << 14);
+
+__device__ __forceinline__ uint32_t lds_peek(uint32_t* p) {
+    return __builtin_amdgcn_readfirstlane(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+}
+__device__ __forceinline__ void lds_post(uint32_t* p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// Barrier of the four consumer wavefronts.  The hardware workgroup barrier would also wait for
+// the producers, which never stop; this one is a monotonic arrival counter in LDS.  LDS executes
+// one wavefront's instructions in order, so the arrival is performed after the wavefront's
+// earlier LDS writes.  Every consumer wavefront executes the same sequence of these barriers.
+__device__ __forceinline__ void cbar(MegaSmem& sm, uint32_t& cgen) {
+    cgen += kMegaWaves;
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(kWaitLds);
+    if ((threadIdx.x & 63) == 0) __hip_atomic_fetch_add(&sm.cbar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    while (int32_t(lds_peek(&sm.cbar) - cgen) < 0) __builtin_amdgcn_s_sleep(1);
+    asm volatile("" ::: "memory");
+}
+
+// Grid barrier: arrive and wait.  A single counter would serialise one device-scope atomic per
+// workgroup (about 10 us for 256 of them under load); instead every workgroup publishes the
+// barrier's sequence number in its own flag word and consumer wavefront 0 of every workgroup
+// polls all flags with one 1 KiB device-scope load.  Sequence numbers keep growing across calls
+// (`epoch`), so flags never need clearing.  Callers have waited for their stores.
+__device__ __forceinline__ void grid_wait(const MegaArgs& a, uint32_t& gen, MegaSmem& sm, uint32_t& cgen) {
+    cbar(sm, cgen);
     gen += 1;
+    if (threadIdx.x == 0 && sm.failed) {  // a bounded wait ran out in this workgroup: tell the one that reports
+        __hip_atomic_store(&a.bar[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+    }
     if (threadIdx.x < 64 && !sm.failed) {
         const uint32_t target = sm.epoch + gen;
         const int lane = threadIdx.x;
@@ -172,35 +217,24 @@ __device__ __forceinline__ void grid_wait(const MegaArgs& a, uint32_t& gen, Mega
             }
         }
     }
-    __syncthreads();
+    cbar(sm, cgen);
 }
 
-// ---- weight ring ---------------------------------------------------------------------------
+// ---- the weight stream -------------------------------------------------------------------------
 // All streaming loads are buffer loads: a wavefront-uniform 128-bit resource (matrix base and
 // size, in scalar registers), a wavefront-uniform 32-bit byte offset (scalar) and the lane's own
-// 16-byte slot.  No per-lane 64-bit address arithmetic, and reads past the end return zero.
+// 16-byte slot.
 constexpr int kAuxNT = 2;  // non-temporal: weights are used once
 constexpr int kOutOfRange = int(0x80000000u);  // lane offset beyond any buffer: the load returns 0, touches nothing
 
-// Where the next 16 fragments come from: NBs tiles (stride `tstride`) x 16/NBs k-steps from sbase.
-struct RingSrc {
-    const bf16x8* w;   // matrix base (wavefront-uniform)
-    uint32_t bytes;    // matrix size
-    int32_t Ks, t0, tstride, nvalid, shift, sbase, smax;
-    __device__ __forceinline__ uint32_t off(int idx) const {
-        const int u = idx >> shift;
-        int i = idx & ((1 << shift) - 1);
-        i = i < nvalid ? i : nvalid - 1;
-        int step = sbase + u;
-        step = step < smax ? step : smax;
-        return (uint32_t(t0 + i * tstride) * uint32_t(Ks) + uint32_t(step)) << 10;
-    }
-};
-
+// One GEMM phase as seen by wavefront pair `wave` of workgroup `wg`: the workgroup's n-tiles are
+// t_first + j * nwg (j < cnt), taken NB at a time ("batch"); the pair's k-steps are [s0, s1).
+// The weights are stored in stream order (batch, then k-step, then tile of the batch): the pair's
+// fragments of the phase are the cnt * (s1 - s0) KiB starting at byte `first` of the matrix.
 struct PhasePlan {
     const bf16x8* w;
-    uint32_t bytes;
-    int32_t Ks, Nt, t_first, cnt, s0, s1;  // this workgroup's tiles: t_first + j*nwg, j < cnt; wavefront's k-steps
+    uint32_t bytes, first;
+    int32_t Ks, Nt, t_first, cnt, s0, s1;
 };
 
 __device__ __forceinline__ PhasePlan plan_phase(const bf16x8* w, int Nt, int Ks, int wg, int nwg, int rot, int wave) {
@@ -210,62 +244,141 @@ __device__ __forceinline__ PhasePlan plan_phase(const bf16x8* w, int Nt, int Ks,
     p.Ks = Ks;
     p.Nt = Nt;
     p.t_first = (wg + rot) % nwg;
-    p.cnt = p.t_first < Nt ? (Nt - p.t_first + nwg - 1) / nwg : 0;
-    p.s0 = (wave * Ks) / kMegaWaves;
-    p.s1 = ((wave + 1) * Ks) / kMegaWaves;
+    const StreamRun r = stream_run(Nt, Ks, nwg, p.t_first, wave);
+    p.cnt = r.cnt;
+    p.s0 = r.s0;
+    p.s1 = r.s1;
+    p.first = uint32_t(r.first) << 10;
     return p;
 }
 
-template <int NB>
-__device__ __forceinline__ RingSrc first_src(const PhasePlan& p, int nwg) {
-    RingSrc s;
-    s.w = p.w;
-    s.bytes = p.bytes;
-    s.Ks = p.Ks;
-    s.t0 = p.cnt > 0 ? p.t_first : 0;
-    s.tstride = p.cnt > 0 ? nwg : 0;
-    s.nvalid = p.cnt > 0 ? (p.cnt < NB ? p.cnt : NB) : 1;
-    s.shift = NB == 1 ? 0 : NB == 2 ? 1 : NB == 4 ? 2 : 3;
-    s.sbase = p.s0;
-    // steps past the wavefront's share re-read its last fragment (a cache hit), never new bytes
-    s.smax = p.s1 > p.s0 ? p.s1 - 1 : (p.s0 < p.Ks ? p.s0 : p.Ks - 1);
-    return s;
+enum StreamPhase { SP_QKV = 0, SP_WO = 1, SP_GU = 2, SP_WD = 3 };
+
+// Phase number ph = 4 * layer + StreamPhase, or 4 * L for the vocabulary head.  The one place
+// that says which matrix and which tile rotation a phase has: producers and consumers both ask
+// here.  (Workgroups with one tile more than the others alternate between the halves of the
+// grid from layer to layer.)
+__device__ __forceinline__ PhasePlan stream_phase(const MegaArgs& a, int ph, int wg, int wave) {
+    const int nwg = a.nwg;
+    if (ph >= 4 * a.L)
+        return plan_phase(reinterpret_cast<const bf16x8*>(a.wbase + a.lm.off), a.lm.Nt, a.lm.Ks, wg, nwg, 0, wave);
+    const int l = ph >> 2, k = ph & 3;
+    const char* lb = a.wbase + a.layer0_off + size_t(l) * a.layer_stride;
+    const int half = nwg / 2;
+    if (k == SP_QKV)
+        return plan_phase(reinterpret_cast<const bf16x8*>(lb + a.qkv.off), a.qkv.Nt, a.qkv.Ks, wg, nwg, (l & 1) * half, wave);
+    if (k == SP_WO)
+        return plan_phase(reinterpret_cast<const bf16x8*>(lb + a.wo.off), a.wo.Nt, a.wo.Ks, wg, nwg, (l & 1) * half, wave);
+    if (k == SP_GU)
+        return plan_phase(reinterpret_cast<const bf16x8*>(lb + a.gu.off), a.gu.Nt, a.gu.Ks, wg, nwg, 0, wave);
+    return plan_phase(reinterpret_cast<const bf16x8*>(lb + a.wd.off), a.wd.Nt, a.wd.Ks, wg, nwg, ((l + 1) & 1) * half, wave);
 }
 
-__device__ __forceinline__ bf16x8 ring_load(__amdgpu_buffer_rsrc_t rs, int lane16, uint32_t off) {
-    return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs, lane16, int(off), kAuxNT));
-}
-
-__device__ __forceinline__ void ring_fill(bf16x8 (&ring)[kRing], const RingSrc& s, int lane) {
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(s.w, s.bytes);
-#pragma unroll
-    for (int idx = 0; idx < kRing; ++idx) ring[idx] = ring_load(rs, lane * 16, s.off(idx));
-}
-
-template <int HALF>
-__device__ __forceinline__ void ring_fill_half(bf16x8 (&ring)[kRing], const RingSrc& s, int lane) {
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(s.w, s.bytes);
-#pragma unroll
-    for (int idx = HALF * (kRing / 2); idx < (HALF + 1) * (kRing / 2); ++idx)
-        ring[idx] = ring_load(rs, lane * 16, s.off(idx));
-}
-
-// B operand (activations) of one k-step: high and low halves for MT row tiles.  `xoff` is the
-// lane's byte offset inside a k-step's block ((kc * rp + row) * 32, or -1 for rows >= r).
-template <int MT>
-__device__ __forceinline__ void load_x(__amdgpu_buffer_rsrc_t xr, const int (&xoff)[MT], int step, int s1, int rp,
-                                       bf16x8 (&xh)[MT], bf16x8 (&xl)[MT]) {
-    const uint32_t soff = uint32_t(step) * uint32_t(rp) * 128u;
-#pragma unroll
-    for (int j = 0; j < MT; ++j) {
-        uint4v hi = {0u, 0u, 0u, 0u}, lo = {0u, 0u, 0u, 0u};
-        if (xoff[j] >= 0 && step < s1) {
-            hi = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[j], int(soff), 0);
-            lo = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[j] + 16, int(soff), 0);
+// ---- producer ----------------------------------------------------------------------------------
+// Walks the stream of wavefront pair w: kRing loads in flight in a static register ring, each
+// arrival written to the next FIFO slot (LDS addresses are dynamic, register indices are not).
+// Waits only for FIFO space.  Once the step has failed (a bounded wait ran out somewhere) nobody
+// waits any more: both sides run through their loops and the kernel ends.
+//
+// A wavefront issues an instruction every few cycles at best, a taken branch costs a pipeline
+// refill, and a fragment is due every ~150 ns: the per-fragment path is a few dozen instructions
+// without a taken branch (the next address is the last one + 1 KiB: stream order), everything
+// else happens once per phase or when the FIFO is full.
+__device__ __forceinline__ void producer(const MegaArgs& a, MegaSmem& sm, int w, int lane, int wg) {
+    const int n_ph = 4 * a.L + 1;
+    int ph = -1;
+    // the next load: resource, scalar offset, fragments left in the phase (0: the stream has ended)
+    __amdgpu_buffer_rsrc_t cur_rs = make_rsrc(a.wbase, 0);
+    uint32_t cur_off = 0, left = 0;
+    auto next_phase = [&]() {
+        while (++ph < n_ph) {
+            const PhasePlan P = stream_phase(a, ph, wg, w);
+            left = uint32_t(P.cnt) * uint32_t(P.s1 - P.s0);
+            if (left == 0) continue;
+            cur_rs = make_rsrc(P.w, P.bytes);
+            cur_off = P.first;
+            if (a.ts && w == 0 && lane == 0 && (ph >> 2) == a.ts_layer) a.ts[size_t(wg) * 32 + 17 + (ph & 3)] = wall_clock64();
+            return;
         }
-        xh[j] = __builtin_bit_cast(bf16x8, hi);
-        xl[j] = __builtin_bit_cast(bf16x8, lo);
+        left = 0;
+        cur_off = 0;
+    };
+    next_phase();
+    uint32_t issued = 0, pushed = 0, head_seen = 0, pofs = 0;
+    bool dead = false;
+    // Every ring step is the same straight line on every path: wait for the slot's load, write it
+    // to LDS (to a dump slot once the stream has ended), issue the slot's next load (an out-of-range
+    // lane offset once the stream has ended: zeros, no memory access).  The scalar bookkeeping in
+    // between may branch, the memory operations never do: the compiler's wait in front of a slot's
+    // use then leaves exactly the other kRing - 1 loads in flight.
+    auto issue = [&](bf16x8& dst) {
+        const bool real = left != 0;
+        int voff = real ? lane * 16 : kOutOfRange;
+        asm volatile("" : "+s"(cur_off), "+v"(voff));  // one load here, not one per incoming path
+        dst = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(cur_rs, voff, int(cur_off), kAuxNT));
+        if (real) {
+            ++issued;
+            cur_off += 1024u;
+            if (__builtin_expect(--left == 0, 0)) next_phase();
+        }
+    };
+    auto push = [&](const bf16x8& v) {
+        const bool real = pushed < issued;
+        if (__builtin_expect(real && !dead && pushed - head_seen >= uint32_t(kFifo), 0)) {
+            uint32_t spins = 0;
+            while (true) {
+                head_seen = lds_peek(&sm.head[w]);
+                if (pushed - head_seen < uint32_t(kFifo)) break;
+                __builtin_amdgcn_s_sleep(1);
+                if (++spins > kLdsSpinLimit || (spins & 63u) == 0 && lds_peek(reinterpret_cast<uint32_t*>(&sm.failed)) != 0) {
+                    dead = true;
+                    lds_post(reinterpret_cast<uint32_t*>(&sm.failed), 1u);
+                    break;
+                }
+            }
+        }
+        asm volatile("" ::: "memory");
+        uint4v* dst = real ? reinterpret_cast<uint4v*>(reinterpret_cast<char*>(&sm.fifo[w][0][lane]) + pofs) : &sm.dump[lane];
+        *dst = __builtin_bit_cast(uint4v, v);
+        asm volatile("" ::: "memory");
+        // LDS runs a wavefront's instructions in order: the count lands after the fragment
+        pushed += real ? 1u : 0u;
+        pofs = real ? (pofs + 1024u == uint32_t(kFifo) * 1024u ? 0u : pofs + 1024u) : pofs;
+        lds_post(&sm.tail[w], pushed);
+    };
+    bf16x8 rg[kRing];
+#pragma unroll
+    for (int j = 0; j < kRing; ++j) issue(rg[j]);
+    while (pushed < issued) {
+#pragma unroll
+        for (int j = 0; j < kRing; ++j) {
+            push(rg[j]);
+            issue(rg[j]);
+        }
     }
+}
+
+// Consumer side of a FIFO (wavefront-uniform state).
+struct FifoC {
+    uint32_t head, tail_seen;  // in fragments
+    uint32_t pos;              // slot of the next fragment
+    bool dead;
+};
+
+// Wait until `need` fragments are there.
+__device__ __forceinline__ void fifo_wait(MegaSmem& sm, FifoC& f, int w, uint32_t need) {
+    if (__builtin_expect(f.tail_seen - f.head >= need, 1)) return;
+    uint32_t spins = 0;
+    while (!f.dead) {
+        f.tail_seen = lds_peek(&sm.tail[w]);
+        if (f.tail_seen - f.head >= need) break;
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > kLdsSpinLimit || (spins & 63u) == 0 && lds_peek(reinterpret_cast<uint32_t*>(&sm.failed)) != 0) {
+            f.dead = true;
+            lds_post(reinterpret_cast<uint32_t*>(&sm.failed), 1u);
+        }
+    }
+    asm volatile("" ::: "memory");
 }
 
 enum MegaEpi { ME_QKV = 0, ME_RESID = 1, ME_SWIGLU = 2, ME_LM = 3 };
@@ -287,18 +400,27 @@ struct EpiArgs {
     __bf16* actfrag;
 };
 
-// ---- one weight-streaming GEMM phase ----------------------------------------------------------
-// out[m][n] = sum_k x[m][k] W[n][k] for this workgroup's n-tiles; the eight wavefronts cut K.
-// RUN_AHEAD = false: the ring is left empty at the end (the caller refills it later); used before
-// the attention phase, which needs the registers.
-template <int NB, int MT, int EPI, bool RUN_AHEAD = true>
+struct NoHook {
+    __device__ __forceinline__ void operator()() const {}
+};
+
+// ---- one GEMM phase, consumer side ---------------------------------------------------------------
+// out[m][n] = sum_k x[m][k] W[n][k] for this workgroup's n-tiles; the four wavefronts cut K.
+// Fragments are popped GROUP at a time (SG k-steps x NB tiles); the activations (B operand) sit
+// in a register ring of XD k-steps, each slot refilled right after its use with the step XD
+// further on, so their latency hides behind a whole ring cycle.  `after_k` runs once, after the
+// last k-loop of the phase and before its reduction and epilogue.
+template <int NB, int MT, int EPI, typename Hook = NoHook>
 __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P, const __bf16* xf, uint32_t xf_bytes,
-                                           const EpiArgs& ea, bf16x8 (&ring)[kRing], const RingSrc& next_first,
-                                           MegaSmem& sm, int wave, int lane) {
-    constexpr int U = kRing / NB;  // k-steps per ring cycle
-    // activation ring: depth in k-steps (one ring cycle, halved where two row tiles would not fit)
-    constexpr int XD = NB == 1 ? (MT == 2 ? 4 : 8) : U;
+                                           const EpiArgs& ea, FifoC& fc, MegaSmem& sm, int wave, int lane,
+                                           uint32_t& cgen, Hook after_k = Hook()) {
+    static_assert(NB <= kGroup && kGroup % NB == 0, "batch width");
+    constexpr int SG = kGroup / NB;  // k-steps per group
+    // k-steps in the activation ring (a multiple of SG; halved where two row tiles meet wide batches)
+    constexpr int XD = (NB == kGroup && MT == 2) ? 4 : 8;
+    static_assert(XD % SG == 0, "ring of whole groups");
     constexpr int COLS = 16 * MT;
+    constexpr int NSUB = NB * MT > 8 ? 2 : 1, NBS = NB / NSUB;  // reduction rounds per batch, tiles per round
     const int tid = opaque_v(threadIdx.x);
     lane = tid & 63;
     const int r = a.r, rp = a.rp;
@@ -344,31 +466,36 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
     }
     const int n_batches = (P.cnt + NB - 1) / NB;
     const int n_steps = P.s1 - P.s0;
-    const int n_chunks = (n_steps + U - 1) / U;
-    const int vtot = n_chunks * U;  // virtual k-steps of one batch (the tail beyond s1 reads zeros)
-    RingSrc src = first_src<NB>(P, a.nwg);
+    const int n_xb = (n_steps + XD - 1) / XD;
+    const int vtot = n_xb * XD;  // virtual k-steps of one batch (the tail beyond s1 reads zeros)
 
-    // The activations (B operand) sit in a second register ring, XD k-steps deep, refilled slot
-    // by slot right after use, exactly like the weight ring.  Loads complete in issue order, so
-    // waiting for the operand of step s only forces loads issued before step s - XD: a full ring
-    // cycle of weight loads stays in flight.  The ring wraps at the end of a batch (every batch
-    // uses the same activations).
     bf16x8 xh[XD][MT], xl[XD][MT];
-    auto load_x = [&](int v, bf16x8 (&h)[MT], bf16x8 (&l)[MT]) {
-        const int step = P.s0 + v;
-        const uint32_t soff = uint32_t(step) * uint32_t(rp) * 128u;
+    // Activations of k-steps past the wavefront's share are whatever the buffer holds there (zeros
+    // past its end): the weight fragments of such steps are zero, so they add nothing.
+    const uint32_t xstep = uint32_t(rp) * 128u;
+    auto load_x = [&](uint32_t soff, bf16x8 (&h)[MT], bf16x8 (&l)[MT]) {
 #pragma unroll
         for (int j = 0; j < MT; ++j) {
-            // no branch: an offset past the end of the buffer makes the load return zeros
-            const int vo = step < P.s1 ? xoff[j] : kOutOfRange;
-            h[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, vo, int(soff), 0));
-            l[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, vo + 16, int(soff), 0));
+            h[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[j], int(soff), 0));
+            l[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[j] + 16, int(soff), 0));
         }
     };
-    if (n_batches > 0 && n_chunks > 0) {
+    const uint32_t xs0 = uint32_t(P.s0) * xstep;
+    uint32_t xs_next = xs0;  // offset of the next k-step to fetch, vn_next its (virtual) index in the batch
+    int vn_next = 0;
+    auto refill = [&](bf16x8 (&h)[MT], bf16x8 (&l)[MT]) {
+        load_x(xs_next, h, l);
+        xs_next += xstep;
+        if (++vn_next == vtot) {  // every batch uses the same activations
+            vn_next = 0;
+            xs_next = xs0;
+        }
+    };
+    if (n_batches > 0 && n_xb > 0) {
 #pragma unroll
-        for (int u = 0; u < XD; ++u) load_x(u, xh[u], xl[u]);
+        for (int u = 0; u < XD; ++u) refill(xh[u], xl[u]);
     }
+    bool hook_done = false;
 
     for (int b = 0; b < n_batches; ++b) {
         floatx4 acc[NB][MT];
@@ -378,48 +505,63 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
             for (int j = 0; j < MT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
         const int nvalid = min(NB, P.cnt - b * NB);
 
-        for (int c = 0; c < n_chunks; ++c) {
-            // source of the refill: next ring cycle of this batch, else next batch, else next phase
-            RingSrc nsrc = src;
-            bool run_ahead = false;  // last ring cycle of the phase: only half the ring runs ahead now
-            if (c + 1 < n_chunks) {
-                nsrc.sbase = src.sbase + U;
-            } else if (b + 1 < n_batches) {
-                nsrc.sbase = P.s0;
-                nsrc.t0 = src.t0 + NB * a.nwg;
-                nsrc.nvalid = min(NB, P.cnt - (b + 1) * NB);
-            } else {
-                nsrc = next_first;
-                run_ahead = true;
-            }
-            const __amdgpu_buffer_rsrc_t nrs = make_rsrc(nsrc.w, nsrc.bytes);
+        for (int xb = 0; xb < n_xb; ++xb) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                constexpr int dummy = 0;
-                (void)dummy;
-                const int slot = u % XD;
+            for (int gg = 0; gg < XD / SG; ++gg) {
+                const int st0 = xb * XD + gg * SG;  // first (virtual) k-step of the group
+                int nvs = n_steps - st0;
+                nvs = nvs > SG ? SG : nvs;
+                if (nvs > 0) {
+                    // the group: nvs k-steps x nvalid tiles, step-major, in consecutive FIFO slots
+                    const uint32_t need = uint32_t(nvs * nvalid);
+                    fifo_wait(sm, fc, wave, need);
+                    bf16x8 fr[SG][NB];
+                    const bool straight = fc.pos + uint32_t(kGroup) <= uint32_t(kFifo);  // no wrap inside the group
+                    if (straight && nvs == SG && (SG == 1 || nvalid == NB)) {
+                        // Static slot offsets.  With one k-step per group the slots of tiles the batch
+                        // does not have hold stale bits: they only reach those tiles' accumulators,
+                        // which nobody reads.
+                        const uint4v* grp = &sm.fifo[wave][fc.pos][lane];
 #pragma unroll
-                for (int i = 0; i < NB; ++i) {
-                    const int idx = u * NB + i;
+                        for (int k = 0; k < kGroup; ++k) fr[k / NB][k % NB] = __builtin_bit_cast(bf16x8, grp[k * 64]);
+                    } else {
 #pragma unroll
-                    for (int j = 0; j < MT; ++j) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[idx], xh[slot][j], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[idx], xl[slot][j], acc[i][j], 0, 0, 0);
+                        for (int u = 0; u < SG; ++u)
+#pragma unroll
+                            for (int i = 0; i < NB; ++i) {
+                                fr[u][i] = __builtin_bit_cast(bf16x8, uint4v{0u, 0u, 0u, 0u});
+                                if (u < nvs && i < nvalid) {
+                                    uint32_t sl = fc.pos + uint32_t(u * nvalid + i);
+                                    sl = sl >= uint32_t(kFifo) ? sl - uint32_t(kFifo) : sl;
+                                    fr[u][i] = __builtin_bit_cast(bf16x8, sm.fifo[wave][sl][lane]);
+                                }
+                            }
                     }
-                    // the part of the ring that must not run ahead yet loads "nothing" (no branch)
-                    const bool hold = run_ahead && !(RUN_AHEAD && idx < kRing / 2);
-                    ring[idx] = ring_load(nrs, hold ? kOutOfRange : lane * 16, nsrc.off(idx));
+                    // LDS runs a wavefront's instructions in order: the slots are read before this lands
+                    asm volatile("" ::: "memory");
+                    fc.head += need;
+                    fc.pos += need;
+                    fc.pos = fc.pos >= uint32_t(kFifo) ? fc.pos - uint32_t(kFifo) : fc.pos;
+                    lds_post(&sm.head[wave], fc.head);
+#pragma unroll
+                    for (int u = 0; u < SG; ++u) {
+                        const int slot = gg * SG + u;
+#pragma unroll
+                        for (int i = 0; i < NB; ++i)
+#pragma unroll
+                            for (int j = 0; j < MT; ++j) {
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr[u][i], xh[slot][j], acc[i][j], 0, 0, 0);
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr[u][i], xl[slot][j], acc[i][j], 0, 0, 0);
+                            }
+                    }
                 }
-                int vn = c * U + u + XD;
-                const bool wraps = vn >= vtot;
-                vn = wraps ? vn - vtot : vn;
-                load_x(vn, xh[slot], xl[slot]);
+#pragma unroll
+                for (int u = 0; u < SG; ++u) refill(xh[gg * SG + u], xl[gg * SG + u]);
             }
-            src = nsrc;
         }
-        if (n_chunks == 0 && b + 1 == n_batches) {
-            // a wavefront without k-steps (K shorter than 8 steps) still moves the first half on
-            if (RUN_AHEAD) ring_fill_half<0>(ring, next_first, lane);
+        if (b + 1 == n_batches) {
+            after_k();
+            hook_done = true;
         }
         if constexpr (EPI != ME_RESID) {
             if (b == 0) {
@@ -434,29 +576,34 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
             }
         }
 
-        // ---- reduce the eight wavefronts (fixed order) --------------------------------------
+        // Reduction and epilogue run on at most eight tile x row-tile blocks at a time (the LDS
+        // staging is sized for that): wide batches with two row tiles take two rounds.
 #pragma unroll
-        for (int i = 0; i < NB; ++i)
+        for (int sb = 0; sb < NSUB; ++sb) {
+        const int nvalid_s = max(0, min(NBS, nvalid - sb * NBS));
+        // ---- reduce the four wavefronts (fixed order) --------------------------------------
+#pragma unroll
+        for (int i = 0; i < NBS; ++i)
 #pragma unroll
             for (int j = 0; j < MT; ++j)
-                *reinterpret_cast<floatx4*>(&sm.red[(wave * NB * MT + i * MT + j) * 256 + lane * 4]) = acc[i][j];
-        __syncthreads();
-        for (int e = tid; e < NB * MT * 256; e += kMegaThreads) {
+                *reinterpret_cast<floatx4*>(&sm.red[(wave * NBS * MT + i * MT + j) * 256 + lane * 4]) = acc[sb * NBS + i][j];
+        cbar(sm, cgen);
+        for (int e = tid; e < NBS * MT * 256; e += kMegaThreads) {
             float s = 0.f;
 #pragma unroll
-            for (int w = 0; w < kMegaWaves; ++w) s += sm.red[w * NB * MT * 256 + e];
+            for (int w = 0; w < kMegaWaves; ++w) s += sm.red[w * NBS * MT * 256 + e];
             const int t = e >> 8, l = (e & 255) >> 2, v = e & 3;
             const int i = t / MT, j = t % MT;
             sm.tile[(i * 16 + (l >> 4) * 4 + v) * COLS + j * 16 + (l & 15)] = s;
         }
-        __syncthreads();
+        cbar(sm, cgen);
 
         // ---- epilogue ----------------------------------------------------------------------------
-        const int tile0 = P.t_first + b * NB * a.nwg;  // tile i of the batch: tile0 + i * nwg
+        const int tile0 = P.t_first + (b * NB + sb * NBS) * a.nwg;  // tile i of the sub-batch: tile0 + i * nwg
         if constexpr (EPI == ME_RESID) {
             // work item: (tile i, row m, half c of the 16 columns); lanes 2q and 2q+1 share a row
             const int c = tid & 1, m = (tid >> 1) % kMaxR, i = tid / (2 * kMaxR);
-            const bool on = i < nvalid && m < r;
+            const bool on = i < nvalid_s && m < r;
             float ssum = 0.f;
             if (on) {
                 const int n0 = (tile0 + i * a.nwg) * 16 + c * 8;
@@ -479,10 +626,10 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
             }
             ssum += __shfl_xor(ssum, 1);
             if (on && c == 0) st_agent(ea.ss_new + size_t(tile0 + i * a.nwg) * kMaxR + m, ssum);
-            static_assert(NB * 2 * kMaxR <= kMegaThreads, "one pass");
+            static_assert(NBS * 2 * kMaxR <= kMegaThreads, "one pass");
         } else if constexpr (EPI == ME_SWIGLU) {
             const int m = tid % kMaxR, i = tid / kMaxR;
-            if (i < nvalid && m < r) {
+            if (i < nvalid_s && m < r) {
                 const float sc = sm.row_scale[m];
                 float av[8];
 #pragma unroll
@@ -496,15 +643,15 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
             }
         } else if constexpr (EPI == ME_LM) {
             if (a.logits) {
-                for (int e = tid; e < NB * 16 * r; e += kMegaThreads) {
-                    const int nl = e % (NB * 16), m = e / (NB * 16);
+                for (int e = tid; e < NBS * 16 * r; e += kMegaThreads) {
+                    const int nl = e % (NBS * 16), m = e / (NBS * 16);
                     const int i = nl >> 4;
                     const int n = (tile0 + i * a.nwg) * 16 + (nl & 15);
-                    if (i < nvalid && n < a.V) a.logits[size_t(m) * a.V + n] = sm.tile[nl * COLS + m] * sm.row_scale[m];
+                    if (i < nvalid_s && n < a.V) a.logits[size_t(m) * a.V + n] = sm.tile[nl * COLS + m] * sm.row_scale[m];
                 }
             }
             constexpr int PARTS = kMegaThreads / COLS;
-            constexpr int ROWS_PER = NB * 16 / PARTS;
+            constexpr int ROWS_PER = NBS * 16 / PARTS;
             static_assert(ROWS_PER >= 1, "rows per thread");
             {
                 const int m = tid % COLS, part = tid / COLS;
@@ -515,7 +662,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                     for (int q = 0; q < ROWS_PER; ++q) {
                         const int nl = part * ROWS_PER + q, i = nl >> 4;
                         const int n = (tile0 + i * a.nwg) * 16 + (nl & 15);
-                        if (i < nvalid && n < a.V) {
+                        if (i < nvalid_s && n < a.V) {
                             const unsigned long long key =
                                 (static_cast<unsigned long long>(float_key(sm.tile[nl * COLS + m] * sc)) << 32) |
                                 (0xffffffffu - uint32_t(n));
@@ -525,7 +672,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                 }
                 sm.part_best[part * COLS + m] = best;
             }
-            __syncthreads();
+            cbar(sm, cgen);
             if (tid < r) {
                 unsigned long long best = sm.wg_best[tid];
                 for (int part = 0; part < PARTS; ++part) {
@@ -538,7 +685,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
             // packed rows: [q heads | k heads | v heads]; in q and k heads row 2p is element p of the
             // head and row 2p+1 its rotation partner p + h/2.  Work item: (tile, row m, which half).
             const int which = tid & 1, m = (tid >> 1) % kMaxR, i = tid / (2 * kMaxR);
-            if (i < nvalid && m < r) {
+            if (i < nvalid_s && m < r) {
                 const int h = a.h, half = h >> 1;
                 const int prow = (tile0 + i * a.nwg) * 16;
                 const float sc = sm.row_scale[m];
@@ -577,7 +724,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
             // consecutive 2-byte slots inside a page row, written as the widest aligned stores
             const int jj = (tid & 1) * 8 + ((tid >> 1) & 7);
             const bool v_lane = ((tid >> 1) % kMaxR) < 8;
-            if (i < nvalid && v_lane && (tile0 + i * a.nwg) * 16 >= a.qd + a.kvd) {
+            if (i < nvalid_s && v_lane && (tile0 + i * a.nwg) * 16 >= a.qd + a.kvd) {
                 const int h = a.h;
                 const int rel = (tile0 + i * a.nwg) * 16 - a.qd - a.kvd + jj;
                 const int head = rel / h, jg = rel % h;
@@ -613,21 +760,16 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                 }
             }
         }
-        __syncthreads();  // red / tile are reused by the next batch
+        cbar(sm, cgen);  // red / tile are reused by the next batch
+        }
     }
-    if (RUN_AHEAD) {
-        if (n_batches == 0) ring_fill_half<0>(ring, next_first, lane);  // no tile here: just move the ring on
-        // second half of the run-ahead: issued after this phase's stores, so that the barrier's wait
-        // for those stores (in-order counter) leaves exactly these kRing/2 loads in flight
-        // (the wavefront that polls the barrier issues its half after the barrier instead)
-        if (wave != 0) ring_fill_half<1>(ring, next_first, lane);
-    }
+    if (!hook_done) after_k();
 }
 
 // ---- chain attention phase ------------------------------------------------------------------------
 // Rows = the G query heads sharing one KV head x the r candidates; row (m, g) sees keys at
 // positions <= ctx_len + m (the target verifies a plain chain, never a tree: Cache Correction,
-// last paragraph).  Task = (kv head, 16-row tile, cut of the page list); the eight wavefronts of
+// last paragraph).  Task = (kv head, 16-row tile, cut of the page list); the four consumer wavefronts of
 // a workgroup take pages round-robin.  Per 16-token page: S^T = K Q^T on the matrix pipe (K page
 // stored in operand order), online softmax per row with wavefront-level reductions,
 // O^T += V^T P^T with the probability tile fed straight from the accumulator registers.
@@ -670,8 +812,8 @@ __device__ __forceinline__ void attn_load_page(const MegaArgs& a, const __bf16* 
 // this (kv head, row tile) merge all cuts.
 template <int H>
 __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t* acount, __bf16* attfrag_l,
-                                                      int G, int rp, int R, int a_splits, int row_tiles, int task,
-                                                      int split, int kvh, int rt) {
+                                            int G, int rp, int R, int a_splits, int row_tiles, int task, int split,
+                                            int kvh, int rt, uint32_t& cgen) {
     constexpr int PART = 16 * (H + 2);
     const int tid = threadIdx.x;
         if (tid < 16) {
@@ -686,7 +828,7 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
             sm.wgt[kMegaWaves * 16 + tid] = mg;
             sm.wgt[(kMegaWaves + 1) * 16 + tid] = l;
         }
-        __syncthreads();
+        cbar(sm, cgen);
         // work item: (row, chunk of 8 head elements); H/8 * 16 <= 256 items
         const int row = tid / (H / 8), ch = tid % (H / 8);
         const bool item = tid < 16 * (H / 8);
@@ -714,14 +856,14 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
+            cbar(sm, cgen);
             int* flag = reinterpret_cast<int*>(&sm.wgt[(kMegaWaves + 2) * 16]);
             if (tid == 0) {
                 const uint32_t prev = __hip_atomic_fetch_add(&acount[kvh * row_tiles + rt], 1u, __ATOMIC_RELAXED,
                                                              __HIP_MEMORY_SCOPE_AGENT);
                 *flag = prev == uint32_t(a_splits) - 1;
             }
-            __syncthreads();
+            cbar(sm, cgen);
             finish = *flag != 0;
             if (finish) {
                 const int S = a_splits;
@@ -735,7 +877,7 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
                     ml[e] = ld_agent(base + size_t(sp) * PART + rw);
                     ml[512 + e] = ld_agent(base + size_t(sp) * PART + 16 + rw);
                 }
-                __syncthreads();
+                cbar(sm, cgen);
                 if (tid < 16) {
                     float mg = -1e30f;
                     for (int sp = 0; sp < S; ++sp) mg = fmaxf(mg, ml[sp * 16 + tid]);
@@ -747,7 +889,7 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
                     }
                     wl[S * 16 + tid] = l;
                 }
-                __syncthreads();
+                cbar(sm, cgen);
                 if (item) {
 #pragma unroll
                     for (int q = 0; q < 8; ++q) v8[q] = 0.f;
@@ -790,7 +932,7 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
 // register file allows next to the query and output tiles.
 template <int H>
 struct AttnBufs {
-    static constexpr int N = H == 128 ? 4 : 8;  // 8 loads per page and head at H = 128: at most ~32 loads in flight per wavefront pay off
+    static constexpr int N = H == 128 ? 2 : 4;  // 8 loads per page and head at H = 128: at most ~32 loads in flight per wavefront pay off
     bf16x8 k[N][H / 32];
     short4v v[N][H / 16];
 };
@@ -834,7 +976,7 @@ __device__ __forceinline__ void attn_page_ids(const MegaArgs& a, int wave, int w
 
 template <int H>
 __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSmem& sm, int wave, int lane, int wg,
-                                           AttnBufs<H>& bf, const int (&pid0)[8], bool (&loaded)[8]) {
+                                           AttnBufs<H>& bf, const int (&pid0)[8], bool (&loaded)[8], uint32_t& cgen) {
     constexpr int ST = H / 32, HT = H / 16, PART = 16 * (H + 2), NBUF = AttnBufs<H>::N;
     const int tid = threadIdx.x;
     const int R = a.G * a.r;
@@ -978,75 +1120,38 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
         for (int i = 0; i < HT; ++i)
 #pragma unroll
             for (int v = 0; v < 4; ++v) mine[32 + col * H + i * 16 + kq * 4 + v] = o[i][v];
-        __syncthreads();
+        cbar(sm, cgen);
         if (a.ts && layer == a.ts_layer && tid == 0) a.ts[size_t(wg) * 32 + 15] = wall_clock64();
         attn_finish<H>(sm, a.apart, a.acount, a.attfrag + size_t(layer) * a.attfrag_stride, a.G, a.rp, R, a.a_splits,
-                       a.row_tiles, task, t.split, kvh, rt);
-        __syncthreads();
+                       a.row_tiles, task, t.split, kvh, rt, cgen);
+        cbar(sm, cgen);
     }
 }
-
-// The attention part of a layer, out of line: it has nothing in common with the GEMM phases
-// (the weight ring is empty while it runs), so it gets a register allocation of its own instead
-// of pushing the streaming loops into spills.  Arguments come straight from the kernel-argument
-// segment.  Returns the barrier generation.
-template <int H>
-__device__ __forceinline__ uint32_t attention_block(const MegaArgs* ap, int l, MegaSmem* smp, uint32_t gen,
-                                                   const int (&pid0)[8]) {
-    const MegaArgs& a = *ap;
-    MegaSmem& sm = *smp;
-    const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int wg = blockIdx.x;
-    const bool tsl = a.ts && l == a.ts_layer && tid == 0;
-    if (tsl) a.ts[size_t(wg) * 32 + 16] = wall_clock64();
-    // page loads of old context first, then wait for everything issued so far: the QKV phase's
-    // stores (queries, new K and V rows) must be acknowledged before the barrier, and the pages
-    // are needed right after it anyway
-    AttnBufs<H> bf;
-    // a pair's second page may not exist: its probabilities are zero, its buffer must be finite
-#pragma unroll
-    for (int i = 0; i < AttnBufs<H>::N; ++i) {
-#pragma unroll
-        for (int q = 0; q < H / 32; ++q) bf.k[i][q] = __builtin_bit_cast(bf16x8, uint4v{0u, 0u, 0u, 0u});
-#pragma unroll
-        for (int q = 0; q < H / 16; ++q) bf.v[i][q] = short4v{0, 0, 0, 0};
-    }
-    bool loaded[8];
-    attn_preload<H>(a, l, wave, lane, wg, bf, pid0, loaded);
-    if (tsl) a.ts[size_t(wg) * 32 + 11] = wall_clock64();
-    store_wait<0>();
-    if (tsl) a.ts[size_t(wg) * 32 + 12] = wall_clock64();
-    grid_wait(a, gen, sm);
-    if (tsl) a.ts[size_t(wg) * 32 + 2] = wall_clock64();
-    attn_phase<H>(a, l, sm, wave, lane, wg, bf, pid0, loaded);
-    return gen;
-}
-
 // ---- the kernel ----------------------------------------------------------------------------------
 template <int MT, int H>
-__global__ __launch_bounds__(kMegaThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_verify(MegaArgs a) {
+__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_verify(MegaArgs a) {
     __shared__ MegaSmem sm;
-    constexpr int NB_QKV = 2, NB_ONE = 1, NB_WIDE = MT == 1 ? 8 : 4;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wg = blockIdx.x, nwg = a.nwg;
-    uint32_t gen = 0;
     if (tid == 0) {
         sm.failed = 0;
+        sm.cbar = 0;
         sm.epoch = __hip_atomic_load(&a.bar[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    if (tid < kMegaWaves) sm.tail[tid] = sm.head[tid] = 0;
     if (tid < kMaxR) sm.wg_best[tid] = 0ull;
-    __syncthreads();
+    __syncthreads();  // the only hardware barrier: producers and consumers part ways here
 
+    if (wave >= kMegaWaves) {
+        producer(a, sm, wave - kMegaWaves, lane, wg);
+        return;
+    }
+
+    uint32_t gen = 0, cgen = 0;
+    FifoC fc = {0u, 0u, 0u, false};
     const int n_dt = a.d >> 4;  // 16-column tiles of the residual stream
     auto layer_base = [&](int l) { return a.wbase + a.layer0_off + size_t(l) * a.layer_stride; };
-    auto mat = [&](const char* base, const MatDesc& m) { return reinterpret_cast<const bf16x8*>(base + m.off); };
-
-    bf16x8 ring[kRing];
-    // start the weight ring on layer 0's QKV matrix before anything else
-    PhasePlan p_qkv = plan_phase(mat(layer_base(0), a.qkv), a.qkv.Nt, a.qkv.Ks, wg, nwg, 0, wave);
-    ring_fill(ring, first_src<NB_QKV>(p_qkv, nwg), lane);
 
     // ---- embed: x0 = E[token], its gained high/low fragments, per-tile sums of squares ----
     {
@@ -1086,22 +1191,12 @@ __global__ __launch_bounds__(kMegaThreads) __attribute__((amdgpu_waves_per_eu(1,
         if (wg == 0 && tid < kMaxR)
             __hip_atomic_store(&a.best[tid], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    store_wait<0>();  // the embed stores are younger than the first ring fill
-    grid_wait(a, gen, sm);
+    store_wait();
+    grid_wait(a, gen, sm, cgen);
 
     int pid0[8];
     attn_page_ids<H>(a, wave, wg, pid0);
     const size_t xres_stride = size_t(kMaxR) * a.d, ss_stride = size_t(n_dt) * kMaxR;
-    // end of a GEMM phase whose ring runs ahead into `nx`: wait for the stores only, cross the
-    // barrier, then let the polling wavefront catch up on the half of the ring it held back
-    auto phase_end = [&](const RingSrc& nx) {
-        if (wave == 0)
-            store_wait<0>();
-        else
-            store_wait<kRing / 2>();
-        grid_wait(a, gen, sm);
-        if (wave == 0) ring_fill_half<1>(ring, nx, lane);
-    };
 #define CARD_TS(i)                                                                  \
     if (a.ts && l == a.ts_layer && tid == 0) a.ts[size_t(wg) * 32 + (i)] = wall_clock64();
     for (int l = 0; l < a.L; ++l) {
@@ -1110,113 +1205,118 @@ __global__ __launch_bounds__(kMegaThreads) __attribute__((amdgpu_waves_per_eu(1,
         const bool last = l + 1 == a.L;
         EpiArgs ea = {};
         ea.layer = l;
-
-        // QKV (+norm scale, rotation, KV write); the ring runs on into the O-projection
-        PhasePlan p_wo = plan_phase(mat(lb, a.wo), a.wo.Nt, a.wo.Ks, wg, nwg, (l & 1) * (nwg / 2), wave);
+        
+        // QKV (+norm scale, rotation, KV write).  Pages that hold only old context do not depend
+        // on this phase: their loads are issued as soon as the k-loop is over, ahead of the
+        // epilogue's stores, and land while the barrier in front of attention is crossed.
+        const PhasePlan p_qkv = stream_phase(a, 4 * l + SP_QKV, wg, wave);
         ea.ss_in = a.ss + v0 * ss_stride;
         ea.qfrag = a.qfrag + size_t(l) * a.qfrag_stride;
         ea.kpool = a.kpool + size_t(l) * a.pool_layer_elems;
         ea.vpool = a.vpool + size_t(l) * a.pool_layer_elems;
+        AttnBufs<H> bf;
+        bool loaded[8];
+        auto preload = [&]() {
+            CARD_TS(11)
+            // a pair's second page may not exist: its probabilities are zero, its buffer must be finite
+#pragma unroll
+            for (int i = 0; i < AttnBufs<H>::N; ++i) {
+#pragma unroll
+                for (int q = 0; q < H / 32; ++q) bf.k[i][q] = __builtin_bit_cast(bf16x8, uint4v{0u, 0u, 0u, 0u});
+#pragma unroll
+                for (int q = 0; q < H / 16; ++q) bf.v[i][q] = short4v{0, 0, 0, 0};
+            }
+            attn_preload<H>(a, l, wave, lane, wg, bf, pid0, loaded);
+            CARD_TS(16)
+        };
         CARD_TS(0)
-        gemm_phase<NB_QKV, MT, ME_QKV, false>(a, p_qkv, a.xfrag + v0 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea,
-                                              ring, first_src<NB_ONE>(p_wo, nwg), sm, wave, lane);
+        gemm_phase<kNbQkv, MT, ME_QKV>(a, p_qkv, a.xfrag + v0 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea, fc,
+                                          sm, wave, lane, cgen, preload);
         CARD_TS(1)
-        gen = attention_block<H>((const MegaArgs*)__builtin_amdgcn_kernarg_segment_ptr(), l, &sm, gen, pid0);
-        // the ring was empty during attention; start it on the O-projection behind the stores
-        // (the wavefront that polls the barrier fills its ring only after the barrier)
-        if (wave != 0) ring_fill(ring, first_src<NB_ONE>(p_wo, nwg), lane);
+        store_wait();
+        CARD_TS(12)
+        grid_wait(a, gen, sm, cgen);
+        CARD_TS(2)
+        attn_phase<H>(a, l, sm, wave, lane, wg, bf, pid0, loaded, cgen);
         CARD_TS(3)
-        if (wave == 0) store_wait<0>(); else store_wait<kRing>();
-        grid_wait(a, gen, sm);
-        if (wave == 0) ring_fill(ring, first_src<NB_ONE>(p_wo, nwg), lane);
+        store_wait();
+        grid_wait(a, gen, sm, cgen);
         CARD_TS(4)
 
         // O-projection + residual -> version v1, gained with the FFN norm's gain
-        PhasePlan p_gu = plan_phase(mat(lb, a.gu), a.gu.Nt, a.gu.Ks, wg, nwg, 0, wave);
+        const PhasePlan p_wo = stream_phase(a, 4 * l + SP_WO, wg, wave);
         ea.xres_old = a.xres + v0 * xres_stride;
         ea.xres_new = a.xres + v1 * xres_stride;
         ea.xfrag_new = a.xfrag + v1 * a.xfrag_stride;
         ea.ss_new = a.ss + v1 * ss_stride;
         ea.gain_next = reinterpret_cast<const float*>(lb + a.g_ffn_off);
-        gemm_phase<NB_ONE, MT, ME_RESID>(a, p_wo, a.attfrag + size_t(l) * a.attfrag_stride, uint32_t(a.attfrag_stride * 2), ea, ring,
-                                         first_src<NB_WIDE>(p_gu, nwg), sm, wave, lane);
+        gemm_phase<kNbOne, MT, ME_RESID>(a, p_wo, a.attfrag + size_t(l) * a.attfrag_stride,
+                                            uint32_t(a.attfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
         CARD_TS(5)
-        phase_end(first_src<NB_WIDE>(p_gu, nwg));
+        store_wait();
+        grid_wait(a, gen, sm, cgen);
         CARD_TS(6)
 
         // gate/up + SwiGLU
-        PhasePlan p_wd = plan_phase(mat(lb, a.wd), a.wd.Nt, a.wd.Ks, wg, nwg, ((l + 1) & 1) * (nwg / 2), wave);
+        const PhasePlan p_gu = stream_phase(a, 4 * l + SP_GU, wg, wave);
         ea.ss_in = a.ss + v1 * ss_stride;
         ea.actfrag = a.actfrag + size_t(l) * a.actfrag_stride;
-        gemm_phase<NB_WIDE, MT, ME_SWIGLU>(a, p_gu, a.xfrag + v1 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea, ring, first_src<NB_ONE>(p_wd, nwg),
-                                           sm, wave, lane);
+        gemm_phase<kNbWide, MT, ME_SWIGLU>(a, p_gu, a.xfrag + v1 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea,
+                                              fc, sm, wave, lane, cgen);
         CARD_TS(7)
-        phase_end(first_src<NB_ONE>(p_wd, nwg));
+        store_wait();
+        grid_wait(a, gen, sm, cgen);
         CARD_TS(8)
 
         // down + residual -> version v2, gained with the next norm's gain
+        const PhasePlan p_wd = stream_phase(a, 4 * l + SP_WD, wg, wave);
         ea.xres_old = a.xres + v1 * xres_stride;
         ea.xres_new = a.xres + v2 * xres_stride;
         ea.xfrag_new = a.xfrag + v2 * a.xfrag_stride;
         ea.ss_new = a.ss + v2 * ss_stride;
         ea.gain_next = last ? reinterpret_cast<const float*>(a.wbase + a.g_final_off)
                             : reinterpret_cast<const float*>(layer_base(l + 1) + a.g_attn_off);
-        if (!last) {
-            p_qkv = plan_phase(mat(layer_base(l + 1), a.qkv), a.qkv.Nt, a.qkv.Ks, wg, nwg, ((l + 1) & 1) * (nwg / 2),
-                               wave);
-            gemm_phase<NB_ONE, MT, ME_RESID>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride, uint32_t(a.actfrag_stride * 2), ea, ring,
-                                             first_src<NB_QKV>(p_qkv, nwg), sm, wave, lane);
-            CARD_TS(9)
-            phase_end(first_src<NB_QKV>(p_qkv, nwg));
-        } else {
-            PhasePlan p_lm = plan_phase(mat(a.wbase, a.lm), a.lm.Nt, a.lm.Ks, wg, nwg, 0, wave);
-            gemm_phase<NB_ONE, MT, ME_RESID>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride, uint32_t(a.actfrag_stride * 2), ea, ring,
-                                             first_src<NB_WIDE>(p_lm, nwg), sm, wave, lane);
-            phase_end(first_src<NB_WIDE>(p_lm, nwg));
-        }
+        gemm_phase<kNbOne, MT, ME_RESID>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride,
+                                            uint32_t(a.actfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
+        CARD_TS(9)
+        store_wait();
+        grid_wait(a, gen, sm, cgen);
         CARD_TS(10)
     }
 
-    // vocabulary head + arg-max; nothing follows, the ring refills from the matrix start (harmless)
+    // vocabulary head + arg-max
     {
-        PhasePlan p_lm = plan_phase(mat(a.wbase, a.lm), a.lm.Nt, a.lm.Ks, wg, nwg, 0, wave);
+                const PhasePlan p_lm = stream_phase(a, 4 * a.L, wg, wave);
         EpiArgs ea = {};
         ea.ss_in = a.ss + size_t(2 * a.L) * ss_stride;
-        RingSrc idle = first_src<NB_WIDE>(p_lm, nwg);
-        gemm_phase<NB_WIDE, MT, ME_LM>(a, p_lm, a.xfrag + size_t(2 * a.L) * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea, ring, idle, sm,
-                                       wave, lane);
+        gemm_phase<kNbWide, MT, ME_LM>(a, p_lm, a.xfrag + size_t(2 * a.L) * a.xfrag_stride,
+                                          uint32_t(a.xfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
         if (tid < a.r && sm.wg_best[tid] != 0ull)
             __hip_atomic_fetch_max(&a.best[tid], sm.wg_best[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    store_wait<0>();
-    grid_wait(a, gen, sm);
-
-    // keep the last ring loads alive until they have landed (they are never consumed)
-    {
-        float sink = 0.f;
-#pragma unroll
-        for (int idx = 0; idx < kRing; ++idx) sink += static_cast<float>(ring[idx][0]);
-        if (sink == 1.2345e-30f) a.rope[0] = sink;
-    }
+    store_wait();
+    grid_wait(a, gen, sm, cgen);
 
     if (wg == 0) {
-        __shared__ int pred[kMaxR + 1];
         if (tid < a.r) {
             const unsigned long long k = __hip_atomic_load(&a.best[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            pred[tid + 1] = int(0xffffffffu - uint32_t(k & 0xffffffffull));
+            sm.pred[tid + 1] = int(0xffffffffu - uint32_t(k & 0xffffffffull));
         }
-        __syncthreads();
+        cbar(sm, cgen);
         if (tid == 0) {
-            pred[0] = a.pending < 0 ? a.cand[0] : a.pending;
+            sm.pred[0] = a.pending < 0 ? a.cand[0] : a.pending;
             int j = 0;
-            while (j < a.r && a.cand[j] == pred[j]) ++j;
-            const bool failed = sm.failed || __hip_atomic_load(&a.bar[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+            while (j < a.r && a.cand[j] == sm.pred[j]) ++j;
+            // weights laid out for another grid size would stream in the wrong order
+            const bool bad_layout = a.stamp[0] != kStampMagic || a.stamp[1] != uint32_t(nwg);
+            const bool failed = bad_layout || sm.failed ||
+                                __hip_atomic_load(&a.bar[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
             a.out->accepted_len = failed ? -1 : j;
-            a.out->correction_token = failed ? -1 : pred[j];
+            a.out->correction_token = failed ? -1 : sm.pred[j];
             a.out->kv_first_slot = a.ctx_len;
             a.out->kv_count = failed ? 0 : j;
         }
-        if (a.row_argmax && tid < a.r) a.row_argmax[tid] = pred[tid + 1];
+        if (a.row_argmax && tid < a.r) a.row_argmax[tid] = sm.pred[tid + 1];
     }
     // the last workgroup to leave re-arms the counters for the next call
     if (tid == 0) {
@@ -1229,5 +1329,6 @@ __global__ __launch_bounds__(kMegaThreads) __attribute__((amdgpu_waves_per_eu(1,
         }
     }
 }
+
 
 }  // namespace card
