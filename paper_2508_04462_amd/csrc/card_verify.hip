@@ -813,7 +813,7 @@ __device__ __forceinline__ void attn_load_page(const MegaArgs& a, const __bf16* 
 template <int H>
 __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t* acount, __bf16* attfrag_l,
                                             int G, int rp, int R, int a_splits, int row_tiles, int task, int split,
-                                            int kvh, int rt, uint32_t& cgen) {
+                                            int kvh, int rt, uint32_t& cgen, unsigned long long* tsp) {
     constexpr int PART = 16 * (H + 2);
     const int tid = threadIdx.x;
         if (tid < 16) {
@@ -857,6 +857,7 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __builtin_amdgcn_s_waitcnt(0);
             cbar(sm, cgen);
+            if (tsp && tid == 0) tsp[29] = wall_clock64();
             int* flag = reinterpret_cast<int*>(&sm.wgt[(kMegaWaves + 2) * 16]);
             if (tid == 0) {
                 const uint32_t prev = __hip_atomic_fetch_add(&acount[kvh * row_tiles + rt], 1u, __ATOMIC_RELAXED,
@@ -865,56 +866,53 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
             }
             cbar(sm, cgen);
             finish = *flag != 0;
+            if (tsp && tid == 0) tsp[30] = wall_clock64();
             if (finish) {
+                // One round trip per ten cuts: every work item fetches its row's (max, sum) pairs
+                // and its own eight output values of those cuts together, then folds them in with a
+                // running maximum.
                 const int S = a_splits;
                 const float* base = apart + size_t(task - split) * PART;
                 const __amdgpu_buffer_rsrc_t prs = make_rsrc(base, uint32_t(S) * PART * 4);
-                float* wl = sm.attn;  // [S][16] weights then [16] totals (S <= 32)
-                // all (cut, row) maxima and sums in one round of device-scope loads (S <= 32)
-                float* ml = sm.attn + 1024;  // [S][16] maxima then [S][16] sums
-                for (int e = tid; e < S * 16; e += kMegaThreads) {
-                    const int sp = e >> 4, rw = e & 15;
-                    ml[e] = ld_agent(base + size_t(sp) * PART + rw);
-                    ml[512 + e] = ld_agent(base + size_t(sp) * PART + 16 + rw);
-                }
-                cbar(sm, cgen);
-                if (tid < 16) {
-                    float mg = -1e30f;
-                    for (int sp = 0; sp < S; ++sp) mg = fmaxf(mg, ml[sp * 16 + tid]);
-                    float l = 0.f;
-                    for (int sp = 0; sp < S; ++sp) {
-                        const float f = __builtin_amdgcn_exp2f(ml[sp * 16 + tid] - mg);
-                        wl[sp * 16 + tid] = f;
-                        l += f * ml[512 + sp * 16 + tid];
-                    }
-                    wl[S * 16 + tid] = l;
-                }
-                cbar(sm, cgen);
-                if (item) {
+                float mg = -1e30f, lg = 0.f;
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) v8[q] = 0.f;
-                    const uint32_t eo = uint32_t(32 + row * H + ch * 8) * 4;
-                    for (int sp = 0; sp < S; sp += 2) {
-                        const bool two = sp + 1 < S;
-                        const uint32_t o0 = uint32_t(sp) * PART * 4 + eo, o1 = two ? o0 + PART * 4 : o0;
-                        const uint4v p0 = __builtin_amdgcn_raw_buffer_load_b128(prs, int(o0), 0, kAuxDev);
-                        const uint4v p1 = __builtin_amdgcn_raw_buffer_load_b128(prs, int(o0 + 16), 0, kAuxDev);
-                        const uint4v p2 = __builtin_amdgcn_raw_buffer_load_b128(prs, int(o1), 0, kAuxDev);
-                        const uint4v p3 = __builtin_amdgcn_raw_buffer_load_b128(prs, int(o1 + 16), 0, kAuxDev);
-                        const float f0 = wl[sp * 16 + row], f1 = two ? wl[(sp + 1) * 16 + row] : 0.f;
+                for (int q = 0; q < 8; ++q) v8[q] = 0.f;
+                constexpr int CH = 10;
+                for (int s0 = 0; s0 < S; s0 += CH) {
+                    uint32_t mw[CH], lw[CH];
+                    uint4v p0[CH], p1[CH];
+#pragma unroll
+                    for (int c = 0; c < CH; ++c) {
+                        // cuts past the last one: an offset beyond the buffer, the loads return zeros
+                        const uint32_t cut = uint32_t(s0 + c) * PART * 4;
+                        const int lane_off = (item && s0 + c < S) ? 0 : kOutOfRange;
+                        mw[c] = __builtin_amdgcn_raw_buffer_load_b32(prs, lane_off + row * 4, int(cut), kAuxDev);
+                        lw[c] = __builtin_amdgcn_raw_buffer_load_b32(prs, lane_off + (16 + row) * 4, int(cut), kAuxDev);
+                        p0[c] = __builtin_amdgcn_raw_buffer_load_b128(prs, lane_off + (32 + row * H + ch * 8) * 4, int(cut), kAuxDev);
+                        p1[c] = __builtin_amdgcn_raw_buffer_load_b128(prs, lane_off + (32 + row * H + ch * 8) * 4 + 16, int(cut), kAuxDev);
+                    }
+                    float mnew = mg;
+#pragma unroll
+                    for (int c = 0; c < CH; ++c)
+                        if (s0 + c < S) mnew = fmaxf(mnew, __uint_as_float(mw[c]));
+                    const float resc = __builtin_amdgcn_exp2f(mg - mnew);
+                    lg *= resc;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) v8[q] *= resc;
+#pragma unroll
+                    for (int c = 0; c < CH; ++c) {
+                        const float f = s0 + c < S ? __builtin_amdgcn_exp2f(__uint_as_float(mw[c]) - mnew) : 0.f;
+                        lg += f * __uint_as_float(lw[c]);
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
-                            v8[q] += f0 * __uint_as_float(p0[q]);
-                            v8[4 + q] += f0 * __uint_as_float(p1[q]);
-                        }
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            v8[q] += f1 * __uint_as_float(p2[q]);
-                            v8[4 + q] += f1 * __uint_as_float(p3[q]);
+                            v8[q] += f * __uint_as_float(p0[c][q]);
+                            v8[4 + q] += f * __uint_as_float(p1[c][q]);
                         }
                     }
-                    inv_l = 1.0f / wl[S * 16 + row];
+                    mg = mnew;
                 }
+                if (item) inv_l = 1.0f / lg;
+                if (tsp && tid == 0) tsp[31] = wall_clock64();
                 if (tid == 0)
                     __hip_atomic_store(&acount[kvh * row_tiles + rt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -1123,7 +1121,8 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
         cbar(sm, cgen);
         if (a.ts && layer == a.ts_layer && tid == 0) a.ts[size_t(wg) * 32 + 15] = wall_clock64();
         attn_finish<H>(sm, a.apart, a.acount, a.attfrag + size_t(layer) * a.attfrag_stride, a.G, a.rp, R, a.a_splits,
-                       a.row_tiles, task, t.split, kvh, rt, cgen);
+                       a.row_tiles, task, t.split, kvh, rt, cgen,
+                       (a.ts && layer == a.ts_layer) ? a.ts + size_t(wg) * 32 : nullptr);
         cbar(sm, cgen);
     }
 }
