@@ -51,10 +51,10 @@ def step_bytes(shape, ctx: int) -> int:
 
 
 def cpu_baseline(shape, seed: int, ctx: int, r: int, cand):
-    """The oracle as it stands, timed on the host: verify steps of the 1-layer and 2-layer
+    """The oracle as it stands, timed on the host: verify steps of the 2-layer and 4-layer
     truncations of the workload (same widths, same context, vocabulary head included), fp32,
-    median of 3 after one warm-up; the full-depth time is extrapolated linearly in depth and
-    labelled as such."""
+    median of 10 after one warm-up (about 10 s of CPU work); the full-depth time is extrapolated
+    linearly in depth and labelled as such."""
     import numpy as np
     from oracle import card_oracle as co
     from oracle.from_inputs import oracle_weights
@@ -68,7 +68,7 @@ def cpu_baseline(shape, seed: int, ctx: int, r: int, cand):
     import card_inputs as ci
     import torch
 
-    s2 = shape.with_layers(2)
+    s2 = shape.with_layers(4)
     dev = "cuda:0" if torch.cuda.is_available() else "cpu"
     w = oracle_weights(s2, seed, dtype=np.float32, device=dev)
     ctx_tokens = ci.uniform_tokens(seed, "ctx_tokens", 0, ctx, shape.vocab).tolist()
@@ -79,23 +79,23 @@ def cpu_baseline(shape, seed: int, ctx: int, r: int, cand):
 
     def timed(cfg):
         ts = []
-        for i in range(4):
+        for i in range(11):
             t = time.time()
             co.verify(cfg, w, kv, ctx, -1, cand, np.float32)
             ts.append(time.time() - t)
         return statistics.median(ts[1:])
 
     t2 = timed(s2)
-    t1 = timed(shape.with_layers(1))
-    per_layer = max(t2 - t1, 0.0)
-    t_full = t1 + (shape.n_layers - 1) * per_layer
+    t1 = timed(shape.with_layers(2))
+    per_layer = max(t2 - t1, 0.0) / 2
+    t_full = t1 + (shape.n_layers - 2) * per_layer
     return {
         "value": r / t_full,
         "unit": "tokens/s",
         "cores": int(threads),
         "kind": "oracle",
-        "sample": (f"oracle verify step (fp32 numpy, r={r}, ctx={ctx}) timed at depth 1 ({t1:.3f} s) and "
-                   f"depth 2 ({t2:.3f} s) of {shape.n_layers}, same widths and vocabulary head; "
+        "sample": (f"oracle verify step (fp32 numpy, r={r}, ctx={ctx}), median of 10 at depth 2 ({t1:.3f} s) and "
+                   f"depth 4 ({t2:.3f} s) of {shape.n_layers}, same widths and vocabulary head; "
                    f"full depth extrapolated linearly to {t_full:.2f} s; untimed oracle prefill {t_prefill:.1f} s"),
     }
 

@@ -82,9 +82,13 @@ size_t card_kv_pool_bytes(const card_model_cfg* cfg, int32_t n_pages);
 
 /* Re-lays one canonical tensor (src_dev, device memory, layout above) into its place inside
  * the packed weight blob (packed_dev, card_packed_weight_bytes(cfg) bytes).  The packed
- * layout stores every matrix as 16x32 tiles in the register order of the gfx950 bf16 matrix
- * instruction so the verify kernels stream it with fully contiguous 1 KiB wavefront loads;
- * values are moved, never changed.  Call once per tensor (per layer for layer tensors). */
+ * layout stores every matrix as 1 KiB fragments (16 rows x 32 columns in the register order of
+ * the gfx950 bf16 matrix instruction), in the order in which the verify kernel's wavefronts
+ * consume them, so each of them streams one contiguous run per matrix; values are moved,
+ * never changed.  That order depends on the number of compute units of the CURRENT device:
+ * pack on the device (or an identical one) that will verify.  The blob records the grid size;
+ * card_verify on a grid of another size reports accepted_len = -1.
+ * Call once per tensor (per layer for layer tensors). */
 int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t layer,
                              const void* src_dev, void* packed_dev, void* stream);
 
@@ -131,8 +135,9 @@ typedef struct card_verify_result {
  *   out_dev            : dev (or device-visible pinned host) card_verify_result
  *   row_argmax_dev     : dev, optional (may be NULL): r int32, arg-max of each row
  * The step runs as one persistent cooperative kernel (one workgroup per compute unit) whose
- * grid barriers have a bounded wait: should the grid ever fail to meet (it cannot when the
- * device is otherwise idle), the kernel still terminates and reports accepted_len = -1.
+ * grid barriers and internal queues have bounded waits: should the grid ever fail to meet (it
+ * cannot when the device is otherwise idle), or the weights have been packed for another grid
+ * size, the kernel still terminates and reports accepted_len = -1.
  * Errors: CARD_EINVAL, CARD_ERANGE (r), CARD_ECAPACITY (ctx_len + r > max_ctx); nothing is
  * enqueued on error.  Token ids are not range-checked on the host (they are on the device:
  * an id outside [0, vocab) is clamped). */
