@@ -14,6 +14,7 @@ constexpr int kMaxR = 32;
 constexpr int kKvBlock = 16;
 // tiles a workgroup accumulates side by side (batch width) per kind of matrix
 constexpr int kNbQkv = 2, kNbOne = 1, kNbWide = 8;
+constexpr int kFlagCopies = 32;  // copies of the barrier flags (256 words each): pollers spread over them
 constexpr uint32_t kStampMagic = 0x43415244u;  // "CARD"
 
 #ifdef __HIPCC__
@@ -162,7 +163,7 @@ inline Layout make_layout(const card_model_cfg* c) {
     L.m_attn_max_splits = 32;
     L.m_apart_off = take(size_t(c->n_kv_heads) * (2 * G) * L.m_attn_max_splits * 16 * (h + 2) * 4);
     L.m_bar_off = take(256);
-    L.m_flags_off = take(4 * 1024);
+    L.m_flags_off = take(size_t(kFlagCopies) * 1024);
     L.m_acount_off = take(size_t(c->n_kv_heads) * (2 * G) * 4);
     L.m_best_off = take(size_t(kMaxR) * 8);
     L.m_rope_off = take(size_t(kMaxR) * h * 4);

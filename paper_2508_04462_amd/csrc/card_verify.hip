@@ -73,7 +73,7 @@ struct MegaArgs {
     float* rope;
     unsigned long long* best;
     uint32_t* bar;     // [1] exit counter, [2] error flag (zero between calls), [3] barrier epoch
-    uint32_t* flags;   // [nwg] last barrier sequence number each workgroup has reached
+    uint32_t* flags;   // [kFlagCopies][256] last barrier sequence number each workgroup has reached
     uint32_t* acount;  // [Hkv * row_tiles] arrival counters of the attention cuts; zero between uses
     const int32_t* cand;
     int32_t pending;
@@ -197,8 +197,11 @@ __device__ __forceinline__ void grid_wait(const MegaArgs& a, uint32_t& gen, Mega
     if (threadIdx.x < 64 && !sm.failed) {
         const uint32_t target = sm.epoch + gen;
         const int lane = threadIdx.x;
-        if (lane == 0) __hip_atomic_store(&a.flags[blockIdx.x], target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const __amdgpu_buffer_rsrc_t frs = make_rsrc(a.flags, uint32_t(a.nwg) * 4);
+        // every copy gets the flag; a workgroup polls the copy of its own residue class, so a
+        // poll round puts 32 readers on a line instead of 256
+        if (lane < kFlagCopies)
+            __hip_atomic_store(&a.flags[lane * 256 + blockIdx.x], target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const __amdgpu_buffer_rsrc_t frs = make_rsrc(a.flags + (blockIdx.x % kFlagCopies) * 256, uint32_t(a.nwg) * 4);
         uint32_t spins = 0;
         while (true) {
             const uint4v f = __builtin_amdgcn_raw_buffer_load_b128(frs, lane * 16, 0, kAuxDev);
