@@ -64,7 +64,7 @@ struct MegaArgs {
     // workspace; "v" = residual version: 0 after embed, 2l+1 after O-proj, 2l+2 after down of layer l
     float* xres;       // [2L+1][32][d]
     __bf16* xfrag;     // [2L+1][xfrag_stride]
-    float* ss;         // [2L+1][d/16][32]
+    float* ss;         // [2L+1][32][d/16]
     __bf16* qfrag;     // [L][Hkv][G*32][h/8][16]
     __bf16* attfrag;   // [L][attfrag_stride]
     __bf16* actfrag;   // [L][actfrag_stride]
@@ -388,7 +388,7 @@ enum MegaEpi { ME_QKV = 0, ME_RESID = 1, ME_SWIGLU = 2, ME_LM = 3 };
 
 struct EpiArgs {
     int32_t layer;
-    const float* ss_in;      // [d/16][32] partial sums of squares of the input rows (norm phases)
+    const float* ss_in;      // [32 rows][d/16] partial sums of squares of the input rows (norm phases)
     // RESID
     const float* xres_old;
     float* xres_new;
@@ -428,38 +428,6 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
     lane = tid & 63;
     const int r = a.r, rp = a.rp;
 
-    // Loads whose results are only needed after the k-loop are issued first: the per-tile sums of
-    // squares behind the RMSNorm scale (SSL lanes per row, SSQ values each) ...
-    constexpr int SSL = kMegaThreads / kMaxR, SSQ = 256 / SSL;
-    float ssv[SSQ];
-    const int ss_row = tid / SSL, ss_sub = tid % SSL, n_part = a.d >> 4;
-    if constexpr (EPI != ME_RESID) {
-#pragma unroll
-        for (int q = 0; q < SSQ; ++q) {
-            const int g = ss_sub + SSL * q;
-            ssv[q] = (ss_row < r && g < n_part) ? ea.ss_in[g * kMaxR + ss_row] : 0.f;
-        }
-    }
-    // ... and the old residual values and next gains of the tile this thread will finish
-    float xo8[8], gn8[8];
-    if constexpr (EPI == ME_RESID) {
-        const int c = tid & 1, m = (tid >> 1) % kMaxR, i = tid / (2 * kMaxR);
-        const bool on = i < min(NB, P.cnt) && m < r;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) xo8[e] = gn8[e] = 0.f;
-        if (on) {
-            const int n0 = (P.t_first + i * a.nwg) * 16 + c * 8;
-            const float4 x0 = *reinterpret_cast<const float4*>(ea.xres_old + size_t(m) * a.d + n0);
-            const float4 x1 = *reinterpret_cast<const float4*>(ea.xres_old + size_t(m) * a.d + n0 + 4);
-            const float4 g0 = *reinterpret_cast<const float4*>(ea.gain_next + n0);
-            const float4 g1 = *reinterpret_cast<const float4*>(ea.gain_next + n0 + 4);
-            xo8[0] = x0.x; xo8[1] = x0.y; xo8[2] = x0.z; xo8[3] = x0.w;
-            xo8[4] = x1.x; xo8[5] = x1.y; xo8[6] = x1.z; xo8[7] = x1.w;
-            gn8[0] = g0.x; gn8[1] = g0.y; gn8[2] = g0.z; gn8[3] = g0.w;
-            gn8[4] = g1.x; gn8[5] = g1.y; gn8[6] = g1.z; gn8[7] = g1.w;
-        }
-    }
-
     const __amdgpu_buffer_rsrc_t xr = make_rsrc(xf, xf_bytes);
     int xoff[MT];
 #pragma unroll
@@ -498,6 +466,40 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
 #pragma unroll
         for (int u = 0; u < XD; ++u) refill(xh[u], xl[u]);
     }
+    // Loads whose results are only needed after the k-loop are issued now, behind the first
+    // activations (loads return in issue order): the per-tile sums of squares behind the RMSNorm
+    // scale (SSL lanes per row, SSQ groups of four tiles each) ...
+    constexpr int SSL = kMegaThreads / kMaxR, SSQ = 8;
+    float4 ssv[SSQ];
+    const int ss_row = tid / SSL, ss_sub = tid % SSL, n_part = a.d >> 4, n_grp = n_part >> 2;
+    if constexpr (EPI != ME_RESID) {
+#pragma unroll
+        for (int q = 0; q < SSQ; ++q) {
+            const int g = ss_sub + SSL * q;
+            ssv[q] = (ss_row < r && g < n_grp) ? *reinterpret_cast<const float4*>(ea.ss_in + size_t(ss_row) * n_part + 4 * g)
+                                               : float4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    // ... and the old residual values and next gains of the tile this thread will finish
+    float xo8[8], gn8[8];
+    if constexpr (EPI == ME_RESID) {
+        const int c = tid & 1, m = (tid >> 1) % kMaxR, i = tid / (2 * kMaxR);
+        const bool on = i < min(NB, P.cnt) && m < r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xo8[e] = gn8[e] = 0.f;
+        if (on) {
+            const int n0 = (P.t_first + i * a.nwg) * 16 + c * 8;
+            const float4 x0 = *reinterpret_cast<const float4*>(ea.xres_old + size_t(m) * a.d + n0);
+            const float4 x1 = *reinterpret_cast<const float4*>(ea.xres_old + size_t(m) * a.d + n0 + 4);
+            const float4 g0 = *reinterpret_cast<const float4*>(ea.gain_next + n0);
+            const float4 g1 = *reinterpret_cast<const float4*>(ea.gain_next + n0 + 4);
+            xo8[0] = x0.x; xo8[1] = x0.y; xo8[2] = x0.z; xo8[3] = x0.w;
+            xo8[4] = x1.x; xo8[5] = x1.y; xo8[6] = x1.z; xo8[7] = x1.w;
+            gn8[0] = g0.x; gn8[1] = g0.y; gn8[2] = g0.z; gn8[3] = g0.w;
+            gn8[4] = g1.x; gn8[5] = g1.y; gn8[6] = g1.z; gn8[7] = g1.w;
+        }
+    }
+
     bool hook_done = false;
 
     for (int b = 0; b < n_batches; ++b) {
@@ -570,9 +572,12 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
             if (b == 0) {
                 float sq = 0.f;
 #pragma unroll
-                for (int q = 0; q < SSQ; ++q) sq += ssv[q];
-                if (n_part > 256 && ss_row < r)
-                    for (int g = ss_sub + 256; g < n_part; g += SSL) sq += ea.ss_in[g * kMaxR + ss_row];
+                for (int q = 0; q < SSQ; ++q) sq += (ssv[q].x + ssv[q].y) + (ssv[q].z + ssv[q].w);
+                if (ss_row < r)
+                    for (int g = ss_sub + SSL * SSQ; g < n_grp; g += SSL) {
+                        const float4 v = *reinterpret_cast<const float4*>(ea.ss_in + size_t(ss_row) * n_part + 4 * g);
+                        sq += (v.x + v.y) + (v.z + v.w);
+                    }
 #pragma unroll
                 for (int o = 1; o < SSL; o <<= 1) sq += __shfl_xor(sq, o);
                 if (ss_sub == 0 && ss_row < r) sm.row_scale[ss_row] = 1.0f / sqrtf(sq * a.inv_d + a.eps);
@@ -628,7 +633,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                 st_dev_frag8(ea.xfrag_new, frag_index(n0, m, rp), gv);
             }
             ssum += __shfl_xor(ssum, 1);
-            if (on && c == 0) st_agent(ea.ss_new + size_t(tile0 + i * a.nwg) * kMaxR + m, ssum);
+            if (on && c == 0) st_agent(ea.ss_new + size_t(m) * (a.d >> 4) + (tile0 + i * a.nwg), ssum);
             static_assert(NBS * 2 * kMaxR <= kMegaThreads, "one pass");
         } else if constexpr (EPI == ME_SWIGLU) {
             const int m = tid % kMaxR, i = tid / kMaxR;
@@ -1180,7 +1185,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
                 st_dev_frag8(a.xfrag, frag_index(n0, m, a.rp), gv);
             }
             ssum += __shfl_xor(ssum, 1);
-            if (on && c == 0) st_agent(a.ss + size_t(t) * kMaxR + m, ssum);
+            if (on && c == 0) st_agent(a.ss + size_t(m) * n_dt + t, ssum);
         }
         // rotation table in fp64 (long contexts stay exact), spread over the grid
         const int half = a.h >> 1;
