@@ -644,7 +644,9 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                 for (int e = 0; e < 8; ++e) {
                     const float g = sm.tile[(i * 16 + e) * COLS + m] * sc;
                     const float u = sm.tile[(i * 16 + 8 + e) * COLS + m] * sc;
-                    av[e] = g / (1.f + expf(-g)) * u;
+                    // SiLU with the hardware exp2 and reciprocal (1 ulp each; the result is rounded to
+                    // bf16 high + low halves afterwards)
+                    av[e] = g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;
                 }
                 const int f0 = (tile0 + i * a.nwg) * 8;
                 st_dev_frag8(ea.actfrag, frag_index(f0, m, rp), av);
