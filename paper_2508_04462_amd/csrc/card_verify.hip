@@ -417,10 +417,12 @@ template <int NB, int MT, int EPI, typename Hook = NoHook>
 __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P, const __bf16* xf, uint32_t xf_bytes,
                                            const EpiArgs& ea, FifoC& fc, MegaSmem& sm, int wave, int lane,
                                            uint32_t& cgen, Hook after_k = Hook()) {
-    static_assert(NB <= kGroup && kGroup % NB == 0, "batch width");
-    constexpr int SG = kGroup / NB;  // k-steps per group
+    // fragments per pop: eight, four where two row tiles leave fewer registers for them
+    constexpr int GRP = (MT == 2 && NB < kGroup) ? kGroup / 2 : kGroup;
+    static_assert(NB <= GRP && GRP % NB == 0, "batch width");
+    constexpr int SG = GRP / NB;  // k-steps per group
     // k-steps in the activation ring (a multiple of SG; halved where two row tiles meet wide batches)
-    constexpr int XD = (NB == kGroup && MT == 2) ? 4 : 8;
+    constexpr int XD = MT == 2 ? 4 : 8;
     static_assert(XD % SG == 0, "ring of whole groups");
     constexpr int COLS = 16 * MT;
     constexpr int NSUB = NB * MT > 8 ? 2 : 1, NBS = NB / NSUB;  // reduction rounds per batch, tiles per round
@@ -521,14 +523,14 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                     const uint32_t need = uint32_t(nvs * nvalid);
                     fifo_wait(sm, fc, wave, need);
                     bf16x8 fr[SG][NB];
-                    const bool straight = fc.pos + uint32_t(kGroup) <= uint32_t(kFifo);  // no wrap inside the group
+                    const bool straight = fc.pos + uint32_t(GRP) <= uint32_t(kFifo);  // no wrap inside the group
                     if (straight && nvs == SG && (SG == 1 || nvalid == NB)) {
                         // Static slot offsets.  With one k-step per group the slots of tiles the batch
                         // does not have hold stale bits: they only reach those tiles' accumulators,
                         // which nobody reads.
                         const uint4v* grp = &sm.fifo[wave][fc.pos][lane];
 #pragma unroll
-                        for (int k = 0; k < kGroup; ++k) fr[k / NB][k % NB] = __builtin_bit_cast(bf16x8, grp[k * 64]);
+                        for (int k = 0; k < GRP; ++k) fr[k / NB][k % NB] = __builtin_bit_cast(bf16x8, grp[k * 64]);
                     } else {
 #pragma unroll
                         for (int u = 0; u < SG; ++u)
