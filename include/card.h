@@ -80,6 +80,16 @@ size_t card_workspace_bytes(const card_model_cfg* cfg);
 /* bytes of ONE of the two page pools (K or V) holding n_pages pages for all layers */
 size_t card_kv_pool_bytes(const card_model_cfg* cfg, int32_t n_pages);
 
+/* Where fragment (n-tile t, k-step s) of a packed matrix with n_tiles x k_steps fragments lives:
+ * its index (in units of 1 KiB) from the start of the matrix, for batch width `batch`
+ * (2 for the fused QKV matrix, 1 for the O and down projections, 8 for gate/up and the
+ * vocabulary head) on a grid of `grid` workgroups.  A pure host function: it is the single
+ * definition of the stream order that card_weights_pack_tensor writes and card_verify reads
+ * (tile t belongs to grid position t % grid; k-step s to wavefront pair floor(4 s / k_steps);
+ * inside a pair: batch of tiles, then k-step, then tile).  Returns -1 on invalid arguments. */
+int64_t card_stream_frag_index(int32_t n_tiles, int32_t k_steps, int32_t batch, int32_t grid, int32_t t,
+                               int32_t s);
+
 /* Re-lays one canonical tensor (src_dev, device memory, layout above) into its place inside
  * the packed weight blob (packed_dev, card_packed_weight_bytes(cfg) bytes).  The packed
  * layout stores every matrix as 1 KiB fragments (16 rows x 32 columns in the register order of

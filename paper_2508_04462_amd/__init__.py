@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     card_packed_weight_bytes,
     card_workspace_bytes,
     card_kv_pool_bytes,
+    card_stream_frag_index,
     card_weights_pack_tensor,
     card_verify,
     card_verify_debug_logits,

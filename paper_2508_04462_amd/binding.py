@@ -66,6 +66,8 @@ lib.card_strerror.argtypes = [C.c_int]
 for _n in ("card_packed_weight_bytes", "card_workspace_bytes"):
     getattr(lib, _n).restype = C.c_size_t
     getattr(lib, _n).argtypes = [_cfgp]
+lib.card_stream_frag_index.restype = C.c_int64
+lib.card_stream_frag_index.argtypes = [C.c_int32] * 6
 lib.card_kv_pool_bytes.restype = C.c_size_t
 lib.card_kv_pool_bytes.argtypes = [_cfgp, C.c_int32]
 lib.card_weights_pack_tensor.restype = C.c_int
@@ -119,6 +121,10 @@ def card_packed_weight_bytes(cfg: CardModelCfg) -> int:
 
 def card_workspace_bytes(cfg: CardModelCfg) -> int:
     return lib.card_workspace_bytes(C.byref(cfg))
+
+
+def card_stream_frag_index(n_tiles: int, k_steps: int, batch: int, grid: int, t: int, s: int) -> int:
+    return lib.card_stream_frag_index(n_tiles, k_steps, batch, grid, t, s)
 
 
 def card_kv_pool_bytes(cfg: CardModelCfg, n_pages: int) -> int:

@@ -190,6 +190,12 @@ size_t card_kv_pool_bytes(const card_model_cfg* cfg, int32_t n_pages) {
     return size_t(cfg->n_layers) * n_pages * cfg->n_kv_heads * 16 * cfg->head_dim * 2;
 }
 
+int64_t card_stream_frag_index(int32_t n_tiles, int32_t k_steps, int32_t batch, int32_t grid, int32_t t, int32_t s) {
+    if (n_tiles <= 0 || k_steps <= 0 || batch <= 0 || grid <= 0 || t < 0 || t >= n_tiles || s < 0 || s >= k_steps)
+        return -1;
+    return stream_frag_index(n_tiles, k_steps, batch, grid, t, s);
+}
+
 int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t layer, const void* src_dev,
                              void* packed_dev, void* stream) {
     if (!src_dev || !packed_dev) return CARD_EINVAL;

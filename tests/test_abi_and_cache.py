@@ -36,6 +36,29 @@ def test_sizes_follow_the_shapes():
     assert card.card_packed_weight_bytes(bad) == 0 and card.card_workspace_bytes(bad) == 0
 
 
+@pytest.mark.parametrize("n_tiles,k_steps,batch,grid", [(384, 128, 2, 256), (256, 448, 1, 256), (1792, 128, 8, 256),
+                                                        (8016, 128, 8, 256), (43, 9, 2, 7), (5, 3, 8, 16), (64, 8, 1, 256)])
+def test_stream_order_is_a_bijection_with_contiguous_runs(n_tiles, k_steps, batch, grid):
+    """The packed order of a matrix: every fragment exactly once, and the fragments of one
+    (grid position, wavefront pair) form ONE run ordered batch, then k-step, then tile."""
+    idx = np.array([[card.card_stream_frag_index(n_tiles, k_steps, batch, grid, t, s) for s in range(k_steps)]
+                    for t in range(n_tiles)], dtype=np.int64)
+    assert sorted(idx.ravel().tolist()) == list(range(n_tiles * k_steps))
+    nxt = 0
+    for p in range(grid):
+        tiles = list(range(p, n_tiles, grid))
+        for w in range(4):
+            s0, s1 = w * k_steps // 4, (w + 1) * k_steps // 4
+            for b in range(0, len(tiles), batch):
+                for s in range(s0, s1):
+                    for t in tiles[b:b + batch]:
+                        assert idx[t, s] == nxt, (p, w, b, s, t)
+                        nxt += 1
+    assert nxt == n_tiles * k_steps
+    assert card.card_stream_frag_index(n_tiles, k_steps, batch, grid, n_tiles, 0) == -1
+    assert card.card_stream_frag_index(n_tiles, k_steps, batch, 0, 0, 0) == -1
+
+
 def test_argument_errors_are_caught_on_the_host():
     cfg = card.make_cfg(ci.SHAPES["tiny"], 256)
     kv = card.CardKV(0x1000, 0x1000, 0x1000, 16, -1)
