@@ -170,8 +170,12 @@ int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weigh
  * max_launches floats), returns the count in *n_host and disables the hook.
  * card_profile_timeline: buf_dev = device array of 32 uint64 per workgroup (256 workgroups), or
  * NULL to switch off; while set, the verify kernel stores 100 MHz timestamps of the phase
- * boundaries of decoder layer `layer` there (start, QKV done, barrier, attention done, barrier,
- * O-proj done, barrier, gate/up done, barrier, down done, barrier). */
+ * boundaries of decoder layer `layer` there.  Slots per workgroup (consumer wavefront 0):
+ * 0 start, 1 QKV done, 2 barrier, 3 attention done, 4 barrier, 5 O-proj done, 6 barrier,
+ * 7 gate/up done, 8 barrier, 9 down done, 10 barrier; 11 end of the QKV k-loop, 16 page
+ * preload issued, 12 QKV stores acknowledged; attention workgroups: 13 page loop entered,
+ * 14 left, 15 wavefronts merged, 29 partial stored, 30 arrival counted, 31 cuts merged;
+ * 17-20 the producer of wavefront pair 0 starts streaming the QKV / O / gate-up / down matrix. */
 int card_profile_enable(int32_t max_launches);
 int card_profile_collect(float* ms_host, int32_t* n_host);
 int card_profile_timeline(void* buf_dev, int32_t layer);
