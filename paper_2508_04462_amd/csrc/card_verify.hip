@@ -818,8 +818,7 @@ __device__ __forceinline__ void attn_load_page(const MegaArgs& a, const __bf16* 
     }
 }
 
-// Second half of an attention task, kept out of line so that its index arithmetic does not
-// compete for registers with the page loop: merge the eight wavefront partials in LDS, then
+// Second half of an attention task: merge the four consumer wavefronts' partials in LDS, then
 // either finish (context not cut) or hand the cut's partial over and let the last workgroup of
 // this (kv head, row tile) merge all cuts.
 template <int H>
@@ -942,12 +941,12 @@ __device__ __forceinline__ void attn_finish(MegaSmem& sm, float* apart, uint32_t
 // register file allows next to the query and output tiles.
 template <int H>
 struct AttnBufs {
-    static constexpr int N = H == 128 ? 2 : 4;  // 8 loads per page and head at H = 128: at most ~32 loads in flight per wavefront pay off
+    static constexpr int N = H == 128 ? 2 : 4;  // 64 registers of the consumer's 256
     bf16x8 k[N][H / 32];
     short4v v[N][H / 16];
 };
 
-// Before the barrier: issue the loads of the first task's first four pages where those hold old
+// Before the barrier: issue the loads of the first task's first pages where those hold old
 // context only (they do not depend on this layer's QKV phase).  loaded[i] tells the phase.
 template <int H>
 __device__ __forceinline__ void attn_preload(const MegaArgs& a, int layer, int wave, int lane, int wg, AttnBufs<H>& bf,
