@@ -1,0 +1,115 @@
+"""The query-and-correct loop end to end (overview figure; Cache Correction): a scripted draft
+fills the shared candidate cache (host C++ cache of libcard) with a small tree whose best path
+follows the target's own greedy text with probability p per token, the target queries the cache
+with the token it has just verified, verifies the returned path with card_verify on the GPU,
+and corrects the cache with what it accepted.  Whatever the draft's hit rate, the emitted text
+must be the target's plain greedy text (lossless at temperature 0), here the CPU oracle's stream
+over its decisive prefix; a miss degrades to a plain decode step (r = 1).
+"""
+import numpy as np
+import pytest
+
+import card_inputs as ci
+from gpu_common import GAP, make_pair
+from oracle import card_oracle as co
+
+pytestmark = pytest.mark.gpu
+TINY = ci.SHAPES["tiny"]
+
+
+def _draft(cache, truth, rng, p, depth, width):
+    """Level 0 = the verified token; level i proposes `width` tokens for position i, node 0 the
+    best-scored one.  The best path is right with probability p per token; when it goes wrong the
+    right token sits on a lower-scored sibling half of the time."""
+    cache.write(0, [truth[0]], [-1], [1.0])
+    alive = True  # the best path still follows the truth
+    for i in range(1, depth):
+        if i >= len(truth):
+            break
+        right = truth[i]
+        wrong = [(right + 1 + k) % TINY.vocab for k in range(width)]
+        good = alive and rng.random() < p
+        toks = [right if good else wrong[0]]
+        sibling_right = alive and not good and rng.random() < 0.5
+        toks.append(right if sibling_right else wrong[1])
+        toks += wrong[2:width]
+        scores = [0.9 ** i] + [0.5 ** i * 0.5 ** k for k in range(1, width)]
+        cache.write(i, toks, [0] * width, scores)
+        alive = good
+
+
+# seeds whose oracle greedy text stays decisive (top-1 / top-2 gap > 0.05) for 10-20 tokens, found
+# by an oracle-only search over seeds 1..42 (about six rows in ten are decisive at this width)
+@pytest.mark.parametrize("p,seed", [(0.3, 11), (0.6, 33), (0.9, 42), (1.0, 11), (0.0, 27)])
+def test_query_verify_correct_loop_is_lossless(p, seed):
+    import paper_2508_04462_amd as card
+
+    shape, n_new, r = TINY, 24, 6
+    tgt, w = make_pair(shape, seed, max_ctx=shape.ctx + n_new + r + 16)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, shape.ctx, shape.vocab).tolist()
+    kv_ref = co.OracleKV.empty(shape, shape.ctx + n_new + r + 16)
+    g0 = co.prefill(shape, w, kv_ref, ctx)
+    want, gaps = co.greedy_decode_cached(shape, w, kv_ref, shape.ctx, g0, n_new)
+    decisive_upto = next((i for i, g in enumerate(gaps) if g <= GAP), n_new)
+    truth = want[: decisive_upto + 1]  # g0 .. the last token every deciding row of which is decisive
+    if len(truth) < 4:
+        pytest.skip("seed without a decisive prefix")
+
+    tgt.prefill(ctx)
+    cache = card.CandidateCache(K=8, max_depth=r)
+    rng = np.random.default_rng(seed)
+    n, pending = shape.ctx, g0  # the oracle's pending token starts the stream on both sides
+    emitted, hits, misses, accepted = [pending], 0, 0, []
+    while len(emitted) < len(truth):
+        e = len(emitted) - 1
+        _draft(cache, truth[e:] + [0] * r, rng, p, r, 4)
+        hit, path, _ = cache.query(pending, r)
+        assert hit and path[0] == pending  # the draft has just written the verified token at level 0
+        hits += 1
+        res = tgt.verify(n, pending, path)
+        acc = res["accepted_len"]
+        assert 1 <= acc <= len(path)  # the key itself is always accepted
+        accepted.append(acc)
+        emitted += path[1:acc] + [res["correction_token"]]
+        n += res["kv_count"]
+        pending = res["correction_token"]
+        cache.correct(path[:acc])
+        # the sibling branch: if the correction token is still in the tree, the next query hits without a new draft
+        hit2, path2, _ = cache.query(pending, r)
+        if hit2 and len(emitted) < len(truth):
+            assert path2[0] == pending
+            res = tgt.verify(n, pending, path2)
+            acc = res["accepted_len"]
+            assert acc >= 1
+            emitted += path2[1:acc] + [res["correction_token"]]
+            n += res["kv_count"]
+            pending = res["correction_token"]
+            cache.correct(path2[:acc])
+        else:
+            misses += 1
+    k = min(len(emitted), len(truth))
+    assert emitted[:k] == truth[:k]
+    if p == 1.0:
+        assert max(accepted) > 1
+    if p == 0.0:  # a draft that is always wrong costs nothing but its own work: one token per step
+        assert all(a == 1 for a in accepted)
+
+
+def test_cache_miss_is_a_plain_decode_step():
+    import paper_2508_04462_amd as card
+
+    shape, seed = TINY, 7
+    tgt, w = make_pair(shape, seed, max_ctx=shape.ctx + 32)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, shape.ctx, shape.vocab).tolist()
+    g0 = tgt.prefill(ctx)
+    cache = card.CandidateCache(K=8, max_depth=4)
+    hit, path, _ = cache.query(g0, 4)
+    assert not hit
+    res = tgt.verify(shape.ctx, g0, [g0])  # r = 1: the pending token alone
+    assert res["accepted_len"] == 1 and res["kv_count"] == 1
+    kv_ref = co.OracleKV.empty(shape, shape.ctx + 32)
+    g0_ref = co.prefill(shape, w, kv_ref, ctx)
+    if g0_ref == g0:
+        ref = co.verify(shape, w, kv_ref, shape.ctx, g0, [g0], keep_logits=True)
+        if ref.row_gap[0] > GAP:
+            assert res["correction_token"] == ref.correction_token
