@@ -191,6 +191,9 @@ def main():
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "verify_latency_us": ms_per_step * 1e3,
+        "verify_latency_us_median_launch": statistics.median(ms_each) * 1e3 if ms_each else None,
+        # planted j cycles uniformly over 0..r: mean accepted length r/2 (asserted per j above)
+        "accepted_tokens_per_s": (r / 2) / (ms_per_step * 1e-3),
         "hbm_fraction_whole_step": kbytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_step": kbytes,
         "higher_is_better": True,

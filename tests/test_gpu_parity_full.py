@@ -82,9 +82,13 @@ def test_tiny_against_stored_oracle_values():
     _run("tiny_seed1.json")
 
 
-def test_full_size_workload_against_stored_oracle_values():
+FULL = sorted(f for f in os.listdir(GOLDEN) if f.startswith("llama8b_seed") and f.endswith(".json"))
+
+
+@pytest.mark.parametrize("golden_name", FULL)
+def test_full_size_workload_against_stored_oracle_values(golden_name):
     """The configuration bench.py times: 8B shape, 1024 tokens of context, r = 8, one workgroup
-    per compute unit; planted prefixes j = 0, 4, 8."""
-    g = _run("llama8b_seed1.json")
+    per compute unit; planted prefixes j = 0, 4, 8; one case per stored seed."""
+    g = _run(golden_name)
     assert g["shape"] == "llama8b" and g["ctx"] == 1024 and g["r"] == 8
     torch.cuda.synchronize()
