@@ -164,3 +164,20 @@ def test_argument_errors_enqueue_nothing(tiny_pair):
     kv = tgt.kv(-1)
     st = card.card_verify(tgt.cfg, None, kv, 0, tgt.cand, 1, tgt.workspace, None, tgt.out, None)
     assert st == card.CARD_EINVAL
+
+
+def test_weights_not_packed_for_this_grid_report_a_failed_step():
+    """The packed blob records the grid size its stream order was laid out for; a blob without
+    that record (here: never packed) makes the step end normally and report failure."""
+    import paper_2508_04462_amd as card
+
+    tgt = card.Target(TINY, 160)
+    tgt.packed.zero_()
+    res = tgt.verify(0, -1, [1, 2, 3])
+    assert res["accepted_len"] == -1 and res["correction_token"] == -1 and res["kv_count"] == 0
+    # the same object works once the weights are there
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    load_synthetic_weights(tgt, TINY, 1)
+    res = tgt.verify(0, -1, [1, 2, 3])
+    assert 1 <= res["accepted_len"] <= 3 and 0 <= res["correction_token"] < TINY.vocab  # row 0 is trusted
