@@ -59,10 +59,10 @@ int grid_size() {
     return cus > 256 ? 256 : cus;
 }
 
-template <int MT, int H>
+template <int MT, int H, bool PK>
 int launch_mega(MegaArgs& a, hipStream_t st) {
     void* params[] = {&a};
-    const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<void*>(k_verify<MT, H>), dim3(a.nwg),
+    const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<void*>(k_verify<MT, H, PK>), dim3(a.nwg),
                                                     dim3(kBlockThreads), params, 0, st);
     return e == hipSuccess ? CARD_OK : CARD_EDEVICE;
 }
@@ -155,8 +155,9 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.ts_layer = g_ts_layer;
     hipStream_t st = as_stream(stream);
     ProfScope ps(st);
-    if (r <= 16) return h == 128 ? launch_mega<1, 128>(a, st) : launch_mega<1, 64>(a, st);
-    return h == 128 ? launch_mega<2, 128>(a, st) : launch_mega<2, 64>(a, st);
+    if (r <= 8) return h == 128 ? launch_mega<1, 128, true>(a, st) : launch_mega<1, 64, true>(a, st);
+    if (r <= 16) return h == 128 ? launch_mega<1, 128, false>(a, st) : launch_mega<1, 64, false>(a, st);
+    return h == 128 ? launch_mega<2, 128, false>(a, st) : launch_mega<2, 64, false>(a, st);
 }
 
 }  // namespace

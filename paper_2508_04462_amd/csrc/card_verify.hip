@@ -45,6 +45,7 @@ constexpr int kProdWaves = kMegaWaves;    // producer wavefront p feeds consumer
 constexpr int kBlockThreads = (kMegaWaves + kProdWaves) * 64;
 constexpr int kRing = 8;                 // weight fragments (1 KiB each) in flight per producer
 constexpr int kFifo = 28;                 // fragment slots per FIFO
+constexpr int kXdPacked = 16;             // k-steps in the activation ring when high and low halves share an operand
 constexpr int kGroup = 8;                 // fragments a consumer pops at a time (SG k-steps x NB tiles)
 constexpr uint32_t kSpinLimit = 1u << 20; // bounded barrier wait: the kernel always terminates
 constexpr uint32_t kLdsSpinLimit = 1u << 24;  // bounded FIFO waits (each poll is an LDS round trip)
@@ -413,7 +414,13 @@ struct NoHook {
 // in a register ring of XD k-steps, each slot refilled right after its use with the step XD
 // further on, so their latency hides behind a whole ring cycle.  `after_k` runs once, after the
 // last k-loop of the phase and before its reduction and epilogue.
-template <int NB, int MT, int EPI, typename Hook = NoHook>
+//
+// PK ("packed halves", r <= 8): the 16 activation columns of the matrix instruction hold the high
+// halves of the (at most eight) rows in columns 0-7 and their low halves in columns 8-15, so one
+// instruction per weight fragment does what otherwise takes two, one operand load per k-step
+// fetches the whole contiguous rp*128-byte run, and the two partial products of a row meet in the
+// reduction.
+template <int NB, int MT, int EPI, bool PK, typename Hook = NoHook>
 __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P, const __bf16* xf, uint32_t xf_bytes,
                                            const EpiArgs& ea, FifoC& fc, MegaSmem& sm, int wave, int lane,
                                            uint32_t& cgen, Hook after_k = Hook()) {
@@ -422,7 +429,8 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
     static_assert(NB <= GRP && GRP % NB == 0, "batch width");
     constexpr int SG = GRP / NB;  // k-steps per group
     // k-steps in the activation ring (a multiple of SG; halved where two row tiles meet wide batches)
-    constexpr int XD = MT == 2 ? 4 : 8;
+    static_assert(!PK || MT == 1, "packed halves: one row tile");
+    constexpr int XD = MT == 2 ? 4 : (PK ? kXdPacked : 8);
     static_assert(XD % SG == 0, "ring of whole groups");
     constexpr int COLS = 16 * MT;
     constexpr int NSUB = NB * MT > 8 ? 2 : 1, NBS = NB / NSUB;  // reduction rounds per batch, tiles per round
@@ -434,8 +442,13 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
     int xoff[MT];
 #pragma unroll
     for (int j = 0; j < MT; ++j) {
-        const int row = j * 16 + (lane & 15);
-        xoff[j] = row < r ? ((lane >> 4) * rp + row) * 32 : kOutOfRange;
+        if constexpr (PK) {
+            const int row = lane & 7, half = (lane >> 3) & 1;
+            xoff[j] = row < r ? ((lane >> 4) * rp + row) * 32 + half * 16 : kOutOfRange;
+        } else {
+            const int row = j * 16 + (lane & 15);
+            xoff[j] = row < r ? ((lane >> 4) * rp + row) * 32 : kOutOfRange;
+        }
     }
     const int n_batches = (P.cnt + NB - 1) / NB;
     const int n_steps = P.s1 - P.s0;
@@ -450,7 +463,8 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
 #pragma unroll
         for (int j = 0; j < MT; ++j) {
             h[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[j], int(soff), 0));
-            l[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[j] + 16, int(soff), 0));
+            if constexpr (!PK)
+                l[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[j] + 16, int(soff), 0));
         }
     };
     const uint32_t xs0 = uint32_t(P.s0) * xstep;
@@ -558,7 +572,8 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
 #pragma unroll
                             for (int j = 0; j < MT; ++j) {
                                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr[u][i], xh[slot][j], acc[i][j], 0, 0, 0);
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr[u][i], xl[slot][j], acc[i][j], 0, 0, 0);
+                                if constexpr (!PK)
+                                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr[u][i], xl[slot][j], acc[i][j], 0, 0, 0);
                             }
                     }
                 }
@@ -604,6 +619,12 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
             for (int w = 0; w < kMegaWaves; ++w) s += sm.red[w * NBS * MT * 256 + e];
             const int t = e >> 8, l = (e & 255) >> 2, v = e & 3;
             const int i = t / MT, j = t % MT;
+            if constexpr (PK) {
+                // column c < 8 carries the high halves' product of row c, column c + 8 the low halves'
+                if ((l & 15) >= 8) continue;
+#pragma unroll
+                for (int w = 0; w < kMegaWaves; ++w) s += sm.red[w * NBS * MT * 256 + e + 32];
+            }
             sm.tile[(i * 16 + (l >> 4) * 4 + v) * COLS + j * 16 + (l & 15)] = s;
         }
         cbar(sm, cgen);
@@ -1138,7 +1159,7 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
     }
 }
 // ---- the kernel ----------------------------------------------------------------------------------
-template <int MT, int H>
+template <int MT, int H, bool PK>
 __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_verify(MegaArgs a) {
     __shared__ MegaSmem sm;
     const int tid = threadIdx.x;
@@ -1240,7 +1261,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
             CARD_TS(16)
         };
         CARD_TS(0)
-        gemm_phase<kNbQkv, MT, ME_QKV>(a, p_qkv, a.xfrag + v0 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea, fc,
+        gemm_phase<kNbQkv, MT, ME_QKV, PK>(a, p_qkv, a.xfrag + v0 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea, fc,
                                           sm, wave, lane, cgen, preload);
         CARD_TS(1)
         store_wait();
@@ -1260,7 +1281,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         ea.xfrag_new = a.xfrag + v1 * a.xfrag_stride;
         ea.ss_new = a.ss + v1 * ss_stride;
         ea.gain_next = reinterpret_cast<const float*>(lb + a.g_ffn_off);
-        gemm_phase<kNbOne, MT, ME_RESID>(a, p_wo, a.attfrag + size_t(l) * a.attfrag_stride,
+        gemm_phase<kNbOne, MT, ME_RESID, PK>(a, p_wo, a.attfrag + size_t(l) * a.attfrag_stride,
                                             uint32_t(a.attfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
         CARD_TS(5)
         store_wait();
@@ -1271,7 +1292,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         const PhasePlan p_gu = stream_phase(a, 4 * l + SP_GU, wg, wave);
         ea.ss_in = a.ss + v1 * ss_stride;
         ea.actfrag = a.actfrag + size_t(l) * a.actfrag_stride;
-        gemm_phase<kNbWide, MT, ME_SWIGLU>(a, p_gu, a.xfrag + v1 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea,
+        gemm_phase<kNbWide, MT, ME_SWIGLU, PK>(a, p_gu, a.xfrag + v1 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea,
                                               fc, sm, wave, lane, cgen);
         CARD_TS(7)
         store_wait();
@@ -1286,7 +1307,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         ea.ss_new = a.ss + v2 * ss_stride;
         ea.gain_next = last ? reinterpret_cast<const float*>(a.wbase + a.g_final_off)
                             : reinterpret_cast<const float*>(layer_base(l + 1) + a.g_attn_off);
-        gemm_phase<kNbOne, MT, ME_RESID>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride,
+        gemm_phase<kNbOne, MT, ME_RESID, PK>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride,
                                             uint32_t(a.actfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
         CARD_TS(9)
         store_wait();
@@ -1299,7 +1320,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
                 const PhasePlan p_lm = stream_phase(a, 4 * a.L, wg, wave);
         EpiArgs ea = {};
         ea.ss_in = a.ss + size_t(2 * a.L) * ss_stride;
-        gemm_phase<kNbWide, MT, ME_LM>(a, p_lm, a.xfrag + size_t(2 * a.L) * a.xfrag_stride,
+        gemm_phase<kNbWide, MT, ME_LM, PK>(a, p_lm, a.xfrag + size_t(2 * a.L) * a.xfrag_stride,
                                           uint32_t(a.xfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
         if (tid < a.r && sm.wg_best[tid] != 0ull)
             __hip_atomic_fetch_max(&a.best[tid], sm.wg_best[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
