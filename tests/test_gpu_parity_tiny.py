@@ -67,10 +67,12 @@ def test_logits_and_argmax_random_candidates(tiny_pair):
     assert res["kv_first_slot"] == TINY.ctx and res["kv_count"] == res["accepted_len"]
 
 
-@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("seed", list(range(1, 21)))
 def test_planted_prefix_all_j(seed):
     """Workload recipe of the small configuration: 128 uniform context tokens, r = 4, the first j
-    candidates are the oracle's greedy tokens; every j in 0..4."""
+    candidates are the oracle's greedy tokens; every j in 0..4, twenty seeds.  The (seed, j) cases
+    whose deciding rows are all decisive carry the bit-exact assertion (printed as "kept"); the
+    others still have to stay within the oracle's top two and the logit tolerance."""
     shape = TINY
     tgt, w = make_pair(shape, seed, max_ctx=160)
     ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, shape.ctx, shape.vocab).tolist()
@@ -92,6 +94,7 @@ def test_planted_prefix_all_j(seed):
             assert res["correction_token"] == ref.correction_token
             assert (res["kv_first_slot"], res["kv_count"]) == (shape.ctx, j)
             checked += 1
+    print(f"seed {seed}: kept {checked} of {shape.r + 1} planted cases for the bit-exact check")
     assert checked >= 1  # j = 0 never depends on a logit
 
 
