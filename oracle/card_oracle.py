@@ -16,8 +16,14 @@ followed by that comparison, written row by row with no blocking or fusion.
 
 Floating point: every operation runs in `dtype` (float64 by default; float32
 for the full-size shapes, where 64-bit weights do not fit in host memory).
-Weights are bf16-representable values widened to `dtype`; the KV cache is kept
-in `dtype`, unrounded.
+Weights are bf16-representable values widened to `dtype`.  The target's KV
+cache is a bf16 cache: what the step stores for later steps (and for its own
+later rows) is K after rotation and V rounded to bf16, round-to-nearest-even
+from the float32 value; every later use reads that stored value widened to
+`dtype`.  That rounding is part of what the step computes, not an error of an
+implementation, so the oracle applies it too (`OracleKV.empty(..., store="bf16")`,
+the default); `store="exact"` keeps the unrounded values (the textbook decoder,
+used by pins that compare with closed forms).
 
 Pins (tests/test_oracle_*.py): row-batched verify == token-by-token decode ==
 cache-free full recompute (a separate code path below); planted-prefix
@@ -44,19 +50,39 @@ class OracleWeights:
     layer: Callable[[int], Dict[str, np.ndarray]]
 
 
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """x rounded to bfloat16 (8 significant bits), ties to even, via its float32 value;
+    returned in x's dtype.  Finite inputs only."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(x.dtype).reshape(x.shape)
+
+
+def cache_value(x: np.ndarray, store: str) -> np.ndarray:
+    """The value a cache of precision `store` ("bf16" or "exact") holds for x."""
+    if store == "bf16":
+        return round_bf16(x)
+    if store == "exact":
+        return x
+    raise ValueError(store)
+
+
 @dataclass
 class OracleKV:
-    """Per layer: K (after rotation) and V for positions [0, capacity), [pos, kv_head, head_dim]."""
+    """Per layer: K (after rotation) and V for positions [0, capacity), [pos, kv_head, head_dim],
+    as the cache holds them (`store`: "bf16" rounds on write, "exact" does not)."""
 
     k: List[np.ndarray] = field(default_factory=list)
     v: List[np.ndarray] = field(default_factory=list)
+    store: str = "bf16"
 
     @staticmethod
-    def empty(cfg, capacity: int, dtype=np.float64) -> "OracleKV":
+    def empty(cfg, capacity: int, dtype=np.float64, store: str = "bf16") -> "OracleKV":
         shp = (capacity, cfg.n_kv_heads, cfg.head_dim)
         return OracleKV(
             [np.zeros(shp, dtype) for _ in range(cfg.n_layers)],
             [np.zeros(shp, dtype) for _ in range(cfg.n_layers)],
+            store,
         )
 
 
@@ -128,8 +154,8 @@ def forward_rows(
         for i in range(r):
             p = start_pos + i
             qi = rope(q[i].reshape(hq, h), p, cfg.rope_theta)
-            kv.k[l][p] = rope(k[i].reshape(hkv, h), p, cfg.rope_theta)
-            kv.v[l][p] = v[i].reshape(hkv, h)
+            kv.k[l][p] = cache_value(rope(k[i].reshape(hkv, h), p, cfg.rope_theta), kv.store)
+            kv.v[l][p] = cache_value(v[i].reshape(hkv, h), kv.store)
             att[i] = attend_row(cfg, qi, kv.k[l][: p + 1], kv.v[l][: p + 1]).reshape(-1)
         x = x + att @ wl["wo"].astype(dtype).T
         u2 = rmsnorm(x, wl["g_ffn"].astype(dtype), dtype(cfg.rms_eps))
@@ -205,10 +231,11 @@ def verify(
 # --------------------------------------------------------------------------- cache-free recompute
 
 
-def full_recompute(cfg, w: OracleWeights, tokens: Sequence[int], dtype=np.float64) -> np.ndarray:
+def full_recompute(cfg, w: OracleWeights, tokens: Sequence[int], dtype=np.float64, store: str = "bf16") -> np.ndarray:
     """Logits [T, vocab] of the whole sequence from scratch: no KV cache, one dense causal mask,
     attention as a masked T x T matrix per head.  Deliberately a different code path from
-    forward_rows (whole-sequence tensors, explicit mask, explicit repetition of KV heads)."""
+    forward_rows (whole-sequence tensors, explicit mask, explicit repetition of KV heads).
+    K and V enter attention as a cache of precision `store` would hold them."""
     t_len = len(tokens)
     hq, hkv, h = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     group = hq // hkv
@@ -228,8 +255,8 @@ def full_recompute(cfg, w: OracleWeights, tokens: Sequence[int], dtype=np.float6
         wl = w.layer(l)
         u = rmsnorm(x, wl["g_attn"].astype(dtype), dtype(cfg.rms_eps))
         q = rot((u @ wl["wq"].astype(dtype).T).reshape(t_len, hq, h))
-        k = rot((u @ wl["wk"].astype(dtype).T).reshape(t_len, hkv, h))
-        v = (u @ wl["wv"].astype(dtype).T).reshape(t_len, hkv, h)
+        k = cache_value(rot((u @ wl["wk"].astype(dtype).T).reshape(t_len, hkv, h)), store)
+        v = cache_value((u @ wl["wv"].astype(dtype).T).reshape(t_len, hkv, h), store)
         k = np.repeat(k, group, axis=1)
         v = np.repeat(v, group, axis=1)
         s = np.einsum("iah,jah->aij", q, k) / np.sqrt(dtype(h)) + mask[None]
@@ -246,13 +273,15 @@ def full_recompute(cfg, w: OracleWeights, tokens: Sequence[int], dtype=np.float6
     return y @ w.lm_head.astype(dtype).T
 
 
-def greedy_decode_bruteforce(cfg, w, ctx_tokens: Sequence[int], n_new: int, dtype=np.float64) -> List[int]:
+def greedy_decode_bruteforce(
+    cfg, w, ctx_tokens: Sequence[int], n_new: int, dtype=np.float64, store: str = "bf16"
+) -> List[int]:
     """Plain autoregressive greedy decoding, one token at a time, recomputing the whole
     sequence each time.  Returns [g0, g1, ..., g_{n_new-1}]."""
     seq = [int(t) for t in ctx_tokens]
     out = []
     for _ in range(n_new):
-        logits = full_recompute(cfg, w, seq, dtype)
+        logits = full_recompute(cfg, w, seq, dtype, store)
         nxt = argmax_lowest(logits[-1])
         out.append(nxt)
         seq.append(nxt)

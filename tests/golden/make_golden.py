@@ -50,7 +50,7 @@ def main():
             "logit_sample": [[float(row[i]) for i in sample_idx] for row in res.logits],
         })
         print(f"case j={j} accepted {res.accepted_len} {time.time() - t0:.0f}s", flush=True)
-    out = {"shape": name, "seed": seed, "ctx": shape.ctx, "r": r, "oracle_dtype": str(np.dtype(dt)),
+    out = {"shape": name, "seed": seed, "ctx": shape.ctx, "r": r, "oracle_dtype": str(np.dtype(dt)), "kv_store": kv.store,
            "greedy": [int(g) for g in greedy], "greedy_gaps": [float(g) for g in gaps],
            "sample_idx": sample_idx, "cases": cases}
     path = os.path.join(ROOT, "tests", "golden", f"{name}_seed{seed}.json")

@@ -5,7 +5,7 @@ All calls go through the C ABI (paper_2508_04462_amd.binding).  Bars:
     top-1/top-2 gap in the oracle exceeds 0.05; otherwise the GPU token must be one of the
     oracle's top two;
   * final-layer logits: per row max|gpu - oracle| / max|oracle| <= 2e-2;
-  * K/V written to the paged cache: within bf16 rounding of the oracle's fp64 values.
+  * K/V written to the paged cache: within one bf16 step of the values the oracle's bf16 cache holds.
 """
 import numpy as np
 import pytest

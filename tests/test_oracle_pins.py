@@ -99,10 +99,12 @@ def test_attend_row_matches_torch_sdpa_gqa():
 # ----------------------------------------------------------------------------- whole forward
 
 
-def _torch_forward(cfg, w, tokens):
+def _torch_forward(cfg, w, tokens, store="exact"):
     """The decoder written with torch library routines only (embedding, rms_norm, linear,
     complex multiply for the rotation, scaled_dot_product_attention with is_causal and
-    enable_gqa, silu) in fp64."""
+    enable_gqa, silu) in fp64.  With store == "bf16", K (after rotation) and V pass through
+    torch's own bfloat16 cast on their way into attention, as a bf16 cache would hold them."""
+    cached = (lambda z: z.float().bfloat16().double()) if store == "bf16" else (lambda z: z)
     t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
     n, hq, hkv, h = len(tokens), cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     x = F.embedding(torch.tensor(tokens, dtype=torch.long), t(w.embed))
@@ -117,8 +119,8 @@ def _torch_forward(cfg, w, tokens):
         wl = w.layer(l)
         u = F.rms_norm(x, (cfg.d_model,), t(wl["g_attn"]), cfg.rms_eps)
         q = rot(F.linear(u, t(wl["wq"])).view(n, hq, h)).transpose(0, 1)[None]
-        k = rot(F.linear(u, t(wl["wk"])).view(n, hkv, h)).transpose(0, 1)[None]
-        v = F.linear(u, t(wl["wv"])).view(n, hkv, h).transpose(0, 1)[None]
+        k = cached(rot(F.linear(u, t(wl["wk"])).view(n, hkv, h))).transpose(0, 1)[None]
+        v = cached(F.linear(u, t(wl["wv"]))).view(n, hkv, h).transpose(0, 1)[None]
         o = F.scaled_dot_product_attention(q, k, v, is_causal=True, enable_gqa=True)
         x = x + F.linear(o[0].transpose(0, 1).reshape(n, hq * h), t(wl["wo"]))
         u2 = F.rms_norm(x, (cfg.d_model,), t(wl["g_ffn"]), cfg.rms_eps)
@@ -126,29 +128,52 @@ def _torch_forward(cfg, w, tokens):
     return F.linear(F.rms_norm(x, (cfg.d_model,), t(w.g_final), cfg.rms_eps), t(w.lm_head)).numpy()
 
 
+@pytest.mark.parametrize("store", ["exact", "bf16"])
 @pytest.mark.parametrize("cfg", [ODD, TINY.with_layers(1)], ids=["odd", "tiny1"])
-def test_forward_matches_torch_library_composition(cfg):
+def test_forward_matches_torch_library_composition(cfg, store):
+    # "exact": the textbook decoder; "bf16": the same with the cache's rounding, done by torch's cast
     w = oracle_weights(cfg, 11, gain_jitter=0.3)
     toks = ci.uniform_tokens(11, "ctx_tokens", 0, 14, cfg.vocab).tolist()
-    ref = _torch_forward(cfg, w, toks)
-    kv = co.OracleKV.empty(cfg, 16)
+    ref = _torch_forward(cfg, w, toks, store)
+    kv = co.OracleKV.empty(cfg, 16, store=store)
     got = co.forward_rows(cfg, w, kv, toks, 0)
     np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-11)
-    np.testing.assert_allclose(co.full_recompute(cfg, w, toks), ref, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(co.full_recompute(cfg, w, toks, store=store), ref, rtol=1e-9, atol=1e-11)
+    if store == "bf16":  # the rounding is not a no-op: the two readings differ well above the tolerance
+        assert np.abs(ref - _torch_forward(cfg, w, toks, "exact")).max() > 1e-5
 
 
-def test_verify_equals_stepwise_decode_equals_full_recompute():
+def test_round_bf16_is_the_library_cast_ties_to_even():
+    rng = _rng(21)
+    x = np.concatenate([rng.normal(size=4000) * 10.0 ** rng.integers(-6, 6, size=4000),
+                        # exact ties between neighbouring bf16 values, both parities, both signs
+                        [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), -(2.0 + 3 * 2.0 ** -7), 0.0, 1.0, -0.375]])
+    for dt in (np.float64, np.float32):
+        ref = torch.from_numpy(x.astype(np.float32)).bfloat16().double().numpy()
+        got = co.round_bf16(x.astype(dt))
+        assert got.dtype == dt
+        np.testing.assert_array_equal(got.astype(np.float64), ref)
+    assert co.round_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0  # tie -> even mantissa
+    assert co.round_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    x2 = rng.normal(size=(3, 5))
+    assert co.cache_value(x2, "exact") is x2
+    with pytest.raises(ValueError):
+        co.cache_value(x2, "fp8")
+
+
+@pytest.mark.parametrize("store", ["bf16", "exact"])
+def test_verify_equals_stepwise_decode_equals_full_recompute(store):
     cfg = ODD
     w = oracle_weights(cfg, 5, gain_jitter=0.3)
     ctx = ci.uniform_tokens(5, "ctx_tokens", 0, cfg.ctx, cfg.vocab).tolist()
     cand = ci.uniform_tokens(5, "cand_tokens", 0, cfg.r, cfg.vocab).tolist()
-    kv_a = co.OracleKV.empty(cfg, 32)
+    kv_a = co.OracleKV.empty(cfg, 32, store=store)
     co.prefill(cfg, w, kv_a, ctx, chunk=4)
     batched = co.forward_rows(cfg, w, kv_a, cand, cfg.ctx)
-    kv_b = co.OracleKV.empty(cfg, 32)
+    kv_b = co.OracleKV.empty(cfg, 32, store=store)
     co.prefill(cfg, w, kv_b, ctx, chunk=9)
     step = np.stack([co.forward_rows(cfg, w, kv_b, [c], cfg.ctx + i)[0] for i, c in enumerate(cand)])
-    full = co.full_recompute(cfg, w, ctx + cand)[cfg.ctx :]
+    full = co.full_recompute(cfg, w, ctx + cand, store=store)[cfg.ctx :]
     np.testing.assert_allclose(batched, step, rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(batched, full, rtol=1e-10, atol=1e-12)
     for l in range(cfg.n_layers):
@@ -160,8 +185,10 @@ def test_float32_oracle_close_to_float64():
     w64 = oracle_weights(cfg, 2)
     w32 = oracle_weights(cfg, 2, dtype=np.float32)
     toks = ci.uniform_tokens(2, "ctx_tokens", 0, 40, cfg.vocab).tolist()
-    a = co.forward_rows(cfg, w64, co.OracleKV.empty(cfg, 40), toks, 0)
-    b = co.forward_rows(cfg, w32, co.OracleKV.empty(cfg, 40, np.float32), toks, 0, np.float32)
+    # unrounded cache: a bf16 store would turn the few-ulp difference of the two precisions into
+    # whole bf16 steps on the elements that sit next to a rounding boundary
+    a = co.forward_rows(cfg, w64, co.OracleKV.empty(cfg, 40, store="exact"), toks, 0)
+    b = co.forward_rows(cfg, w32, co.OracleKV.empty(cfg, 40, np.float32, store="exact"), toks, 0, np.float32)
     assert b.dtype == np.float32
     assert np.abs(a - b).max() < 2e-5 * np.abs(a).max()
 
