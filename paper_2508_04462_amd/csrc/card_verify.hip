@@ -45,7 +45,6 @@ constexpr int kProdWaves = kMegaWaves;    // producer wavefront p feeds consumer
 constexpr int kBlockThreads = (kMegaWaves + kProdWaves) * 64;
 constexpr int kRing = 8;                 // weight fragments (1 KiB each) in flight per producer
 constexpr int kFifo = 28;                 // fragment slots per FIFO
-constexpr int kXdPacked = 16;             // k-steps in the activation ring when high and low halves share an operand
 constexpr int kGroup = 8;                 // fragments a consumer pops at a time (SG k-steps x NB tiles)
 constexpr uint32_t kSpinLimit = 1u << 20; // bounded barrier wait: the kernel always terminates
 constexpr uint32_t kLdsSpinLimit = 1u << 24;  // bounded FIFO waits (each poll is an LDS round trip)
@@ -419,7 +418,7 @@ struct NoHook {
 // halves of the (at most eight) rows in columns 0-7 and their low halves in columns 8-15, so one
 // instruction per weight fragment does what otherwise takes two, one operand load per k-step
 // fetches the whole contiguous rp*128-byte run, and the two partial products of a row meet in the
-// reduction.
+// reduction.  (The ring stays eight k-steps deep: sixteen measured 3 % slower.)
 template <int NB, int MT, int EPI, bool PK, typename Hook = NoHook>
 __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P, const __bf16* xf, uint32_t xf_bytes,
                                            const EpiArgs& ea, FifoC& fc, MegaSmem& sm, int wave, int lane,
@@ -430,7 +429,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
     constexpr int SG = GRP / NB;  // k-steps per group
     // k-steps in the activation ring (a multiple of SG; halved where two row tiles meet wide batches)
     static_assert(!PK || MT == 1, "packed halves: one row tile");
-    constexpr int XD = MT == 2 ? 4 : (PK ? kXdPacked : 8);
+    constexpr int XD = MT == 2 ? 4 : 8;
     static_assert(XD % SG == 0, "ring of whole groups");
     constexpr int COLS = 16 * MT;
     constexpr int NSUB = NB * MT > 8 ? 2 : 1, NBS = NB / NSUB;  // reduction rounds per batch, tiles per round
