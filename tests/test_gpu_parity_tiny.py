@@ -143,6 +143,26 @@ def test_chained_steps_reproduce_greedy_stream(tiny_pair):
     assert emitted[:k] == want[:k]
 
 
+@pytest.mark.parametrize("r_small,r_big", [(8, 9), (5, 16), (8, 17), (16, 17)])
+def test_row_count_code_paths_agree_on_shared_rows(r_small, r_big):
+    """The kernel has one instantiation for r <= 8 (high and low activation halves packed into one
+    matrix operand), one for r <= 16 and one for r <= 32 (two row tiles).  A chain is causal, so
+    the first rows of a longer chain must come out as the shorter chain's rows, whatever
+    instantiation computes them (up to the order of the fp32 sums)."""
+    shape = MID
+    tgt, _ = make_pair(shape, 13, max_ctx=160, gain_jitter=0.2)
+    toks = ci.uniform_tokens(13, "ctx_tokens", 0, 61 + r_big, shape.vocab).tolist()
+    tgt.prefill(toks[:61], chunk=23)
+    big = tgt.verify(61, -1, toks[61:61 + r_big], want_logits=True)
+    small = tgt.verify(61, -1, toks[61:61 + r_small], want_logits=True)
+    a, b = small["logits"].double().numpy(), big["logits"].double().numpy()[:r_small]
+    assert np.abs(a - b).max() <= 1e-4 * np.abs(a).max()
+    for i in range(r_small):  # the same arg-max wherever the shorter chain's row is not a near-tie
+        top = np.sort(a[i])[-2:]
+        if top[1] - top[0] > 1e-3 * np.abs(a).max():
+            assert small["row_argmax"][i] == big["row_argmax"][i]
+
+
 def test_results_are_deterministic_run_to_run(tiny_pair):
     tgt, w, ctx, kv, g0, g0_gpu = tiny_pair
     cand = ci.uniform_tokens(1, "cand_tokens", 9, 8, TINY.vocab).tolist()
