@@ -22,6 +22,9 @@ from gpu_common import GAP, shuffled_pages
 pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 LOGIT_TOL = 2e-2
+# The stated bar is 2e-2; with the cache precision equal on both sides the path measures 4e-4 to
+# 8e-4 at full depth, so a regression shows long before the bar: the full-size cases also hold 4e-3.
+LOGIT_TOL_FULL = 4e-3
 
 
 def _prefix_accept(pending, cand, row_argmax):
@@ -32,7 +35,7 @@ def _prefix_accept(pending, cand, row_argmax):
     return j, pred[j]
 
 
-def _run(golden_name):
+def _run(golden_name, logit_tol=LOGIT_TOL):
     import paper_2508_04462_amd as card
     from paper_2508_04462_amd.synthetic import load_synthetic_weights
 
@@ -69,11 +72,11 @@ def _run(golden_name):
         got = res["logits"][:, idx].double().numpy()
         ref = np.asarray(case["logit_sample"], dtype=np.float64)
         err = np.abs(got - ref).max(axis=1) / np.asarray(case["row_absmax"])
-        assert err.max() <= LOGIT_TOL, (case["j"], err.tolist())
+        assert err.max() <= logit_tol, (case["j"], err.tolist())
         # the row maximum itself (not among the samples unless it is a greedy token)
         full = res["logits"].double().numpy()
         assert np.all(np.abs(np.abs(full).max(axis=1) - np.asarray(case["row_absmax"])) / np.asarray(case["row_absmax"])
-                      <= LOGIT_TOL)
+                      <= logit_tol)
     assert checked_rows > 0
     return g
 
@@ -89,6 +92,6 @@ FULL = sorted(f for f in os.listdir(GOLDEN) if f.startswith("llama8b_seed") and 
 def test_full_size_workload_against_stored_oracle_values(golden_name):
     """The configuration bench.py times: 8B shape, 1024 tokens of context, r = 8, one workgroup
     per compute unit; planted prefixes j = 0, 4, 8; one case per stored seed."""
-    g = _run(golden_name)
-    assert g["shape"] == "llama8b" and g["ctx"] == 1024 and g["r"] == 8
+    g = _run(golden_name, LOGIT_TOL_FULL)
+    assert g["shape"] == "llama8b" and g["ctx"] == 1024 and g["r"] == 8 and g.get("kv_store", "bf16") == "bf16"
     torch.cuda.synchronize()
