@@ -108,7 +108,9 @@ int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t 
  * ((l * n_pages + p) * n_kv_heads) * 16 * head_dim elements.  Token position t lives in page
  * block_table[t / 16], slot t % 16.  Inside a page both K (after rotation) and V are stored in
  * the operand order of the gfx950 matrix instructions that consume them (use card_kv_gather to
- * read them back in plain order).
+ * read them back in plain order).  K and V are rounded to bf16 (nearest even) from their fp32
+ * values when they are written; later rows of the same call and all later calls read the rounded
+ * values.
  * ---------------------------------------------------------------------------------------- */
 typedef struct card_kv {
     void* k_pages;              /* dev */
