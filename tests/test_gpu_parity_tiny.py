@@ -118,6 +118,26 @@ def test_shapes_mid_model(r, ctx_len):
     assert np.abs(k.numpy() - ref_k).max() <= 2.0 ** -7 * np.abs(ref_k).max()
 
 
+@pytest.mark.parametrize("r,ctx_len", [(8, 2100), (5, 4090)])
+def test_long_context_many_cuts(r, ctx_len):
+    """Contexts long enough that the page list of a (kv head, row tile) is cut into more pieces
+    than one merge round fetches (17 and 29 cuts against 10 per round), with workgroups whose
+    wavefronts walk more pages than they hold buffers for (refills inside the loop)."""
+    shape = MID
+    max_ctx = (ctx_len + r + 15) // 16 * 16
+    tgt, w = make_pair(shape, 17, max_ctx=max_ctx, gain_jitter=0.2)
+    toks = ci.uniform_tokens(17, "ctx_tokens", r, ctx_len + r, shape.vocab).tolist()
+    kv = co.OracleKV.empty(shape, max_ctx)
+    co.prefill(shape, w, kv, toks[:ctx_len], chunk=256)
+    tgt.prefill(toks[:ctx_len])
+    ref = co.verify(shape, w, kv, ctx_len, -1, toks[ctx_len:], keep_logits=True)
+    res = tgt.verify(ctx_len, -1, toks[ctx_len:], want_logits=True)
+    assert logits_rel_err(res["logits"], ref.logits) <= 2e-2
+    assert _check_rows(res, ref.logits) > 0
+    k, v = tgt.kv_gather(shape.n_layers - 1, ctx_len, r)
+    assert np.abs(k.numpy() - kv.k[-1][ctx_len: ctx_len + r]).max() <= 2.0 ** -7 * np.abs(kv.k[-1][:ctx_len + r]).max()
+
+
 def test_chained_steps_reproduce_greedy_stream(tiny_pair):
     """Several verify calls in a row, each starting from the previous result, emit exactly the
     oracle's greedy continuation as long as the stream stays decisive."""
