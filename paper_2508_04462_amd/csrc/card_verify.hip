@@ -423,15 +423,17 @@ template <int NB, int MT, int EPI, bool PK, typename Hook = NoHook>
 __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P, const __bf16* xf, uint32_t xf_bytes,
                                            const EpiArgs& ea, FifoC& fc, MegaSmem& sm, int wave, int lane,
                                            uint32_t& cgen, Hook after_k = Hook()) {
-    // fragments per pop: eight; four in narrow batches outside the packed-halves mode, where every
-    // k-step holds two or four activation operands (r = 16: 3.68 -> 3.59 ms at the 8B shape)
-    constexpr int GRP = (!PK && NB < kGroup) ? kGroup / 2 : kGroup;
+    // fragments per pop: eight; outside the packed-halves mode every k-step holds two (r <= 16) or
+    // four (r <= 32) activation operands, and smaller groups and rings leave the registers for
+    // them: four fragments in narrow batches at r <= 16 (8B shape, r = 16: 3.68 -> 3.59 ms), one
+    // k-step of the batch (at least two fragments) at r <= 32 (r = 32: 4.81 -> 4.39 ms)
+    constexpr int GRP = PK ? kGroup : (MT == 2 ? (NB < 2 ? 2 : NB) : (NB < kGroup ? kGroup / 2 : kGroup));
     static_assert(NB <= GRP && GRP % NB == 0, "batch width");
     constexpr int SG = GRP / NB;  // k-steps per group
-    // k-steps in the activation ring (a multiple of SG): eight single-operand steps, or four of
-    // two to four operands each
+    // k-steps in the activation ring (a multiple of SG): eight single-operand steps, four
+    // two-operand steps, two four-operand steps
     static_assert(!PK || MT == 1, "packed halves: one row tile");
-    constexpr int XD = PK ? 8 : 4;
+    constexpr int XD = PK ? 8 : (MT == 2 ? 2 : 4);
     static_assert(XD % SG == 0, "ring of whole groups");
     constexpr int COLS = 16 * MT;
     constexpr int NSUB = NB * MT > 8 ? 2 : 1, NBS = NB / NSUB;  // reduction rounds per batch, tiles per round
