@@ -827,19 +827,30 @@ __device__ __forceinline__ AttnTask attn_task(const MegaArgs& a, int task) {
 }
 
 template <int H>
-__device__ __forceinline__ void attn_load_page(const MegaArgs& a, const __bf16* kpool, const __bf16* vpool, int kvh,
-                                               int pid, int lane, bf16x8 (&kf)[H / 32], short4v (&vf)[H / 16]) {
+__device__ __forceinline__ void attn_load_k(const MegaArgs& a, const __bf16* kpool, int kvh, int pid, int lane,
+                                            bf16x8 (&kf)[H / 32]) {
     const size_t base = (size_t(pid) * a.Hkv + kvh) * (16 * H);
     const bf16x8* kp = reinterpret_cast<const bf16x8*>(kpool + base) + lane;
-    const uint4v* vp = reinterpret_cast<const uint4v*>(vpool + base) + lane;
 #pragma unroll
     for (int st = 0; st < H / 32; ++st) kf[st] = kp[st * 64];
+}
+template <int H>
+__device__ __forceinline__ void attn_load_v(const MegaArgs& a, const __bf16* vpool, int kvh, int pid, int lane,
+                                            short4v (&vf)[H / 16]) {
+    const size_t base = (size_t(pid) * a.Hkv + kvh) * (16 * H);
+    const uint4v* vp = reinterpret_cast<const uint4v*>(vpool + base) + lane;
 #pragma unroll
     for (int i = 0; i < H / 32; ++i) {  // one 16-byte load = the operands of two 16-row tiles
         const uint4v w = vp[i * 64];
         vf[2 * i] = __builtin_bit_cast(short4v, uint2v{w[0], w[1]});
         vf[2 * i + 1] = __builtin_bit_cast(short4v, uint2v{w[2], w[3]});
     }
+}
+template <int H>
+__device__ __forceinline__ void attn_load_page(const MegaArgs& a, const __bf16* kpool, const __bf16* vpool, int kvh,
+                                               int pid, int lane, bf16x8 (&kf)[H / 32], short4v (&vf)[H / 16]) {
+    attn_load_k<H>(a, kpool, kvh, pid, lane, kf);
+    attn_load_v<H>(a, vpool, kvh, pid, lane, vf);
 }
 
 // Second half of an attention task: merge the four consumer wavefronts' partials in LDS, then
@@ -1055,8 +1066,10 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
 
         // Two pages per round: one max / sum reduction across the lane groups and one rescale of
         // the output tile serve 32 keys.  Scores are in log2 units (the query carries log2(e)/sqrt(h)).
+        // `scores_done` runs once the K operands have been consumed: the refill of those registers
+        // starts there, a softmax and an output update ahead of the refill of V
         auto use_two = [&](int pga, const bf16x8 (&ka)[ST], const short4v (&va)[HT], int pgb, const bf16x8 (&kb)[ST],
-                           const short4v (&vb)[HT]) {
+                           const short4v (&vb)[HT], auto&& scores_done) {
             floatx4 sa = floatx4{0.f, 0.f, 0.f, 0.f}, sb = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
@@ -1065,6 +1078,7 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
                 sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[st], ql[st], sa, 0, 0, 0);
                 sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[st], ql[st], sb, 0, 0, 0);
             }
+            scores_done();
             float pmax = -1e30f;
             bool oka[4], okb[4];
 #pragma unroll
@@ -1124,11 +1138,17 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
 #pragma unroll
             for (int i = 0; i < NBUF; i += 2) {
                 if (pg < t.pg1) {
-                    use_two(pg, bf.k[i], bf.v[i], pg + kMegaWaves, bf.k[i + 1], bf.v[i + 1]);
+                    use_two(pg, bf.k[i], bf.v[i], pg + kMegaWaves, bf.k[i + 1], bf.v[i + 1], [&]() {
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            const int nx = pg + (NBUF + q) * kMegaWaves;
+                            if (nx < t.pg1) attn_load_k<H>(a, kpool, kvh, pid_nx[q], lane, bf.k[i + q]);
+                        }
+                    });
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
                         const int nx = pg + (NBUF + q) * kMegaWaves;
-                        if (nx < t.pg1) attn_load_page<H>(a, kpool, vpool, kvh, pid_nx[q], lane, bf.k[i + q], bf.v[i + q]);
+                        if (nx < t.pg1) attn_load_v<H>(a, vpool, kvh, pid_nx[q], lane, bf.v[i + q]);
                     }
                     // ids for the refills after these: behind the page loads in the queue, they will
                     // have arrived a round later
