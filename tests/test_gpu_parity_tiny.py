@@ -118,13 +118,13 @@ def test_shapes_mid_model(r, ctx_len):
     assert np.abs(k.numpy() - ref_k).max() <= 2.0 ** -7 * np.abs(ref_k).max()
 
 
-@pytest.mark.parametrize("shape,r,ctx_len", [(MID, 8, 2100), (MID, 5, 4090), (TINY, 4, 3000)],
-                         ids=["mid-8-2100", "mid-5-4090", "tiny-4-3000"])
+@pytest.mark.parametrize("shape,r,ctx_len", [(MID, 8, 2100), (MID, 5, 4090), (TINY, 4, 3000), (TINY, 3, 9000)],
+                         ids=["mid-8-2100", "mid-5-4090", "tiny-4-3000", "tiny-3-9000"])
 def test_long_context_many_cuts(shape, r, ctx_len):
     """Contexts long enough that the page list of a (kv head, row tile) is cut into more pieces
     than one merge round fetches (17 and 29 cuts against 10 per round), with workgroups whose
     wavefronts walk more pages than they hold buffers for (refills inside the loop); head size
-    64 with 12 cuts as well."""
+    64 with 12 cuts, and with the 32 cuts the workspace allows and refills, as well."""
     max_ctx = (ctx_len + r + 15) // 16 * 16
     tgt, w = make_pair(shape, 17, max_ctx=max_ctx, gain_jitter=0.2)
     toks = ci.uniform_tokens(17, "ctx_tokens", r, ctx_len + r, shape.vocab).tolist()
