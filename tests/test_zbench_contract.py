@@ -1,0 +1,41 @@
+"""The benchmark's output contract, on a short run: one JSON line with the fields the driver
+reads, a roofline object against the HBM peak, and a refusal of more than one GPU."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _run(*flags):
+    return subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *flags], cwd=ROOT, capture_output=True,
+                          text=True, timeout=600)
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    p = _run("--gpus", "2")
+    assert p.returncode != 0
+    assert "ONE GPU" in p.stderr and p.stdout.strip() == ""
+
+
+@pytest.mark.gpu
+def test_short_run_prints_one_json_line_with_the_contract_fields():
+    p = _run("--steps", "6", "--warmup", "2", "--no-cpu-baseline")
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [ln for ln in p.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["metric"] == "verified_tokens_per_s" and d["unit"] == "tokens/s"
+    assert d["n_gpus"] == 1 and d["steps"] == 6 and d["warmup"] == 2
+    assert d["higher_is_better"] is True and d["vs_baseline"] is None and d["data"] == "synthetic"
+    assert "workload" in d["config"] and "model" not in d["config"]
+    assert abs(d["value"] - 8 / (d["ms_per_step"] * 1e-3)) <= 1e-6 * d["value"]  # r = 8 rows per step
+    rf = d["roofline"]
+    assert rf["bound"] == "hbm" and rf["unit"] == "GB/s" and rf["peak"] == 8000.0
+    assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-9
+    assert 0.2 < rf["frac"] < 1.0
+    assert abs(rf["achieved"] - d["algorithmic_bytes_per_step"] / (rf["avg_launch_us"] * 1e-6) / 1e9) <= 1e-6 * rf["achieved"]
+    assert rf["traffic"] is None or rf["traffic"] >= 0.9 * d["algorithmic_bytes_per_step"]
