@@ -22,10 +22,15 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 
 @pytest.mark.gpu
-def test_short_run_prints_one_json_line_with_the_contract_fields():
-    p = _run("--steps", "6", "--warmup", "2", "--no-cpu-baseline")
-    assert p.returncode == 0, p.stderr[-2000:]
-    lines = [ln for ln in p.stdout.splitlines() if ln.strip()]
+def test_short_run_prints_one_json_line_with_the_contract_fields(monkeypatch, capsys):
+    # in this process: run as a child of a test process that has already used the GPU, bench.py's
+    # first cooperative launch came back with a device error
+    import runpy
+
+    monkeypatch.setattr(sys, "argv", ["bench.py", "--steps", "6", "--warmup", "2", "--no-cpu-baseline"])
+    monkeypatch.chdir(ROOT)
+    runpy.run_path(os.path.join(ROOT, "bench.py"), run_name="__main__")
+    lines = [ln for ln in capsys.readouterr().out.splitlines() if ln.strip()]
     assert len(lines) == 1
     d = json.loads(lines[0])
     assert d["metric"] == "verified_tokens_per_s" and d["unit"] == "tokens/s"
