@@ -150,9 +150,13 @@ typedef struct card_verify_result {
  * grid barriers and internal queues have bounded waits: should the grid ever fail to meet (it
  * cannot when the device is otherwise idle), or the weights have been packed for another grid
  * size, the kernel still terminates and reports accepted_len = -1.
- * Errors: CARD_EINVAL, CARD_ERANGE (r), CARD_ECAPACITY (ctx_len + r > max_ctx); nothing is
- * enqueued on error.  Token ids are not range-checked on the host (they are on the device:
- * an id outside [0, vocab) is clamped). */
+ * Errors: CARD_EINVAL, CARD_ERANGE (r), CARD_ECAPACITY (ctx_len + r > max_ctx), CARD_EDEVICE
+ * (the cooperative launch was refused); nothing is enqueued on error.  One process per GPU: while
+ * a process that has launched this kernel is alive, the runtime refuses the cooperative launch
+ * of a second process on the same GPU (observed on MI355X / ROCm 7.2), and that process's calls
+ * return CARD_EDEVICE.  Several targets, streams and threads inside one process are fine.
+ * Token ids are not range-checked on the host (they are on the device: an id outside
+ * [0, vocab) is clamped). */
 int card_verify(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
                 int32_t ctx_len, const int32_t* cand_tokens_dev, int32_t r, void* workspace_dev,
                 void* stream, card_verify_result* out_dev, int32_t* row_argmax_dev);
