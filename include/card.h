@@ -46,8 +46,9 @@ const char* card_strerror(int status);
  * Model description.  Decoder-only, pre-norm: RMSNorm, rotary embedding with half-split
  * pairing, grouped-query attention, SwiGLU feed-forward, untied vocabulary head, no biases
  * (the LLaMA / Qwen families named in Experimental Setup, "Models and Datasets").
- * Constraints: head_dim in {64, 128}; d_model, n_q_heads*head_dim and d_ffn multiples of 16;
- * n_q_heads a multiple of n_kv_heads; kv_block == 16; 1 <= max_r <= 32.
+ * Constraints: head_dim in {64, 128}; d_model a multiple of 64; d_ffn a multiple of 8;
+ * n_q_heads a multiple of n_kv_heads; kv_block == 16; max_ctx a positive multiple of 16;
+ * 1 <= max_r <= 32; every packed matrix below 4 GiB; 0 <= grid_wgs <= 256.
  * ---------------------------------------------------------------------------------------- */
 typedef struct card_model_cfg {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
@@ -55,6 +56,11 @@ typedef struct card_model_cfg {
     int32_t kv_block; /* tokens per KV page: 16                                             */
     int32_t max_ctx;  /* capacity of the block table in tokens (multiple of kv_block)       */
     int32_t max_r;    /* largest r a call may pass (<= 32)                                  */
+    int32_t grid_wgs; /* workgroups of the verify kernel: 0 = one per compute unit (at most
+                         256); a smaller number leaves the other compute units to kernels the
+                         caller runs beside it (the draft model of the paper runs in parallel
+                         with the target: CARD Design, first paragraph).  The packed weight
+                         order depends on it: pack and verify with the same value.            */
 } card_model_cfg;
 
 /* Tensors of the canonical (caller-side) weight set. Matrices are bf16, row-major
@@ -110,7 +116,11 @@ int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t 
  * the operand order of the gfx950 matrix instructions that consume them (use card_kv_gather to
  * read them back in plain order).  K and V are rounded to bf16 (nearest even) from their fp32
  * values when they are written; later rows of the same call and all later calls read the rounded
- * values.
+ * values.  The pools need no initialisation: positions [0, ctx_len) must have been written by
+ * earlier calls, and a call that writes the first slot of a page also clears that page's slots
+ * behind the ones it writes, so no step ever multiplies a zero probability with bits it did not
+ * store.  One layer of a pool (n_pages * n_kv_heads * 16 * head_dim * 2 bytes) must stay below
+ * 4 GiB.
  * ---------------------------------------------------------------------------------------- */
 typedef struct card_kv {
     void* k_pages;              /* dev */
@@ -141,22 +151,24 @@ typedef struct card_verify_result {
  *   packed_weights_dev : blob filled by card_weights_pack_tensor
  *   kv                 : host struct (read during the call only)
  *   cand_tokens_dev    : dev, r int32 token ids in [0, vocab)
- *   workspace_dev      : dev, card_workspace_bytes(cfg) bytes; the caller zeroes it once after
- *                        allocation (and again after a call reported CARD_EDEVICE or
+ *   workspace_dev      : dev, card_workspace_bytes(cfg) bytes, prepared by card_workspace_init
+ *                        once after allocation (and again after a call reported CARD_EDEVICE or
  *                        accepted_len < 0); calls sharing a workspace must not overlap
  *   out_dev            : dev (or device-visible pinned host) card_verify_result
  *   row_argmax_dev     : dev, optional (may be NULL): r int32, arg-max of each row
- * The step runs as one persistent cooperative kernel (one workgroup per compute unit) whose
- * grid barriers and internal queues have bounded waits: should the grid ever fail to meet (it
- * cannot when the device is otherwise idle), or the weights have been packed for another grid
- * size, the kernel still terminates and reports accepted_len = -1.
+ * The step runs as one persistent kernel, one workgroup per compute unit (or cfg->grid_wgs of
+ * them), whose workgroups meet at flag barriers in the workspace; every wait is bounded.  The
+ * step ends normally and reports accepted_len = -1, correction_token = -1, kv_count = 0 when
+ *   - the grid failed to meet (other work held compute units for longer than the waits last:
+ *     run nothing else on the compute units this kernel is to use),
+ *   - the weights were packed for another grid size,
+ *   - the workspace was never prepared by card_workspace_init,
+ *   - a candidate token id lies outside [0, vocab) (ids live in device memory, so the host
+ *     cannot check them; the forward then ran on a clamped id and its result is void).
  * Errors: CARD_EINVAL, CARD_ERANGE (r), CARD_ECAPACITY (ctx_len + r > max_ctx), CARD_EDEVICE
- * (the cooperative launch was refused); nothing is enqueued on error.  One process per GPU: while
- * a process that has launched this kernel is alive, the runtime refuses the cooperative launch
- * of a second process on the same GPU (observed on MI355X / ROCm 7.2), and that process's calls
- * return CARD_EDEVICE.  Several targets, streams and threads inside one process are fine.
- * Token ids are not range-checked on the host (they are on the device: an id outside
- * [0, vocab) is clamped). */
+ * (the device cannot hold one workgroup of the kernel per compute unit, or the launch failed);
+ * nothing is enqueued on error.  Calls from several threads are fine as long as calls that
+ * share a workspace do not overlap; all calls of a thread go to the thread's current device. */
 int card_verify(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
                 int32_t ctx_len, const int32_t* cand_tokens_dev, int32_t r, void* workspace_dev,
                 void* stream, card_verify_result* out_dev, int32_t* row_argmax_dev);
@@ -169,11 +181,19 @@ int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weigh
                              card_verify_result* out_dev, int32_t* row_argmax_dev,
                              float* logits_dev);
 
-/* Measurement hooks (benchmark only; not thread-safe; allocate no device memory).
+/* Prepares a freshly allocated workspace (card_workspace_bytes(cfg) bytes, dev, 16-byte aligned):
+ * clears all of it (barrier words, flags and arrival counters start at zero; hand-over bytes
+ * that a step never writes must be finite) and marks it as prepared.  Asynchronous on `stream`;
+ * allocates nothing. */
+int card_workspace_init(const card_model_cfg* cfg, void* workspace_dev, void* stream);
+
+/* Measurement hooks (benchmark only; one user at a time; allocate no device memory).
  * card_profile_enable: while enabled, card_verify brackets its kernel with a pair of HIP
  * events recorded on the call's stream, up to max_launches pairs; card_profile_collect waits
  * for them, writes each launch's duration in milliseconds to ms_host (host array of
  * max_launches floats), returns the count in *n_host and disables the hook.
+ * card_profile_disable switches the hook off and destroys its events: call it before the process
+ * ends (the library never touches the HIP runtime from a static destructor).
  * card_profile_timeline: buf_dev = device array of 32 uint64 per workgroup (256 workgroups), or
  * NULL to switch off; while set, the verify kernel stores 100 MHz timestamps of the phase
  * boundaries of decoder layer `layer` there.  Slots per workgroup (consumer wavefront 0):
@@ -184,6 +204,7 @@ int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weigh
  * 17-20 the producer of wavefront pair 0 starts streaming the QKV / O / gate-up / down matrix. */
 int card_profile_enable(int32_t max_launches);
 int card_profile_collect(float* ms_host, int32_t* n_host);
+int card_profile_disable(void);
 int card_profile_timeline(void* buf_dev, int32_t layer);
 
 /* Test helper: copies K (rotated) and V of positions [first_slot, first_slot+count) of one

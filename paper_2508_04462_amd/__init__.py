@@ -2,8 +2,9 @@
 
 The work is done by libcard.so (hand-written HIP for gfx950 behind the C ABI of
 include/card.h).  This package only marshals arguments; PyTorch supplies device
-memory and streams.  Importing the package loads the library and fails loudly if
-it has not been built (python -m paper_2508_04462_amd.build).
+memory and streams.  The library is opened at the first call of any entry point and
+that call fails loudly (ImportError) if it has not been built
+(python -m paper_2508_04462_amd.build): there is no other implementation behind it.
 """
 from .binding import (  # noqa: F401
     CARD_OK,
@@ -29,6 +30,8 @@ from .binding import (  # noqa: F401
     card_verify_debug_logits,
     card_kv_gather,
     card_profile_enable,
+    card_profile_disable,
+    card_workspace_init,
     card_profile_collect,
     card_profile_timeline,
     card_cache_create,

@@ -27,7 +27,7 @@ class CardModelCfg(C.Structure):
         ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
         ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
         ("vocab", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float),
-        ("kv_block", C.c_int32), ("max_ctx", C.c_int32), ("max_r", C.c_int32),
+        ("kv_block", C.c_int32), ("max_ctx", C.c_int32), ("max_r", C.c_int32), ("grid_wgs", C.c_int32),
     ]
 
 
@@ -53,53 +53,76 @@ def _load() -> C.CDLL:
     return C.CDLL(lib_path)
 
 
-lib = _load()
-
 _P = C.c_void_p
 _cfgp = C.POINTER(CardModelCfg)
 _kvp = C.POINTER(CardKV)
 _i32p = C.POINTER(C.c_int32)
 _f32p = C.POINTER(C.c_float)
 
-lib.card_strerror.restype = C.c_char_p
-lib.card_strerror.argtypes = [C.c_int]
-for _n in ("card_packed_weight_bytes", "card_workspace_bytes"):
-    getattr(lib, _n).restype = C.c_size_t
-    getattr(lib, _n).argtypes = [_cfgp]
-lib.card_stream_frag_index.restype = C.c_int64
-lib.card_stream_frag_index.argtypes = [C.c_int32] * 6
-lib.card_kv_pool_bytes.restype = C.c_size_t
-lib.card_kv_pool_bytes.argtypes = [_cfgp, C.c_int32]
-lib.card_weights_pack_tensor.restype = C.c_int
-lib.card_weights_pack_tensor.argtypes = [_cfgp, C.c_int32, C.c_int32, _P, _P, _P]
-lib.card_verify.restype = C.c_int
-lib.card_verify.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P]
-lib.card_verify_debug_logits.restype = C.c_int
-lib.card_verify_debug_logits.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P, _P]
-lib.card_kv_gather.restype = C.c_int
-lib.card_kv_gather.argtypes = [_cfgp, _kvp, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P]
-lib.card_profile_enable.restype = C.c_int
-lib.card_profile_enable.argtypes = [C.c_int32]
-lib.card_profile_timeline.restype = C.c_int
-lib.card_profile_timeline.argtypes = [_P, C.c_int32]
-lib.card_profile_collect.restype = C.c_int
-lib.card_profile_collect.argtypes = [_f32p, _i32p]
-lib.card_cache_create.restype = C.c_int
-lib.card_cache_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(_P)]
-lib.card_cache_destroy.restype = None
-lib.card_cache_destroy.argtypes = [_P]
-lib.card_cache_write.restype = C.c_int
-lib.card_cache_write.argtypes = [_P, C.c_int64, C.c_int32, C.c_int32, _i32p, _i32p, _f32p]
-lib.card_cache_query.restype = C.c_int
-lib.card_cache_query.argtypes = [_P, C.c_int32, C.c_int32, _i32p, _i32p, _f32p]
-lib.card_cache_correct.restype = C.c_int
-lib.card_cache_correct.argtypes = [_P, _i32p, C.c_int32]
-lib.card_cache_epoch.restype = C.c_int64
-lib.card_cache_epoch.argtypes = [_P]
-lib.card_cache_depth.restype = C.c_int32
-lib.card_cache_depth.argtypes = [_P]
-lib.card_cache_read_level.restype = C.c_int
-lib.card_cache_read_level.argtypes = [_P, C.c_int32, _i32p, _i32p, _f32p]
+
+def _declare(lib: C.CDLL) -> C.CDLL:
+    """Result and argument types of every entry point of include/card.h."""
+    lib.card_strerror.restype = C.c_char_p
+    lib.card_strerror.argtypes = [C.c_int]
+    for _n in ("card_packed_weight_bytes", "card_workspace_bytes"):
+        getattr(lib, _n).restype = C.c_size_t
+        getattr(lib, _n).argtypes = [_cfgp]
+    lib.card_stream_frag_index.restype = C.c_int64
+    lib.card_stream_frag_index.argtypes = [C.c_int32] * 6
+    lib.card_kv_pool_bytes.restype = C.c_size_t
+    lib.card_kv_pool_bytes.argtypes = [_cfgp, C.c_int32]
+    lib.card_weights_pack_tensor.restype = C.c_int
+    lib.card_weights_pack_tensor.argtypes = [_cfgp, C.c_int32, C.c_int32, _P, _P, _P]
+    lib.card_workspace_init.restype = C.c_int
+    lib.card_workspace_init.argtypes = [_cfgp, _P, _P]
+    lib.card_verify.restype = C.c_int
+    lib.card_verify.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P]
+    lib.card_verify_debug_logits.restype = C.c_int
+    lib.card_verify_debug_logits.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P, _P]
+    lib.card_kv_gather.restype = C.c_int
+    lib.card_kv_gather.argtypes = [_cfgp, _kvp, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P]
+    lib.card_profile_enable.restype = C.c_int
+    lib.card_profile_enable.argtypes = [C.c_int32]
+    lib.card_profile_disable.restype = C.c_int
+    lib.card_profile_disable.argtypes = []
+    lib.card_profile_timeline.restype = C.c_int
+    lib.card_profile_timeline.argtypes = [_P, C.c_int32]
+    lib.card_profile_collect.restype = C.c_int
+    lib.card_profile_collect.argtypes = [_f32p, _i32p]
+    lib.card_cache_create.restype = C.c_int
+    lib.card_cache_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(_P)]
+    lib.card_cache_destroy.restype = None
+    lib.card_cache_destroy.argtypes = [_P]
+    lib.card_cache_write.restype = C.c_int
+    lib.card_cache_write.argtypes = [_P, C.c_int64, C.c_int32, C.c_int32, _i32p, _i32p, _f32p]
+    lib.card_cache_query.restype = C.c_int
+    lib.card_cache_query.argtypes = [_P, C.c_int32, C.c_int32, _i32p, _i32p, _f32p]
+    lib.card_cache_correct.restype = C.c_int
+    lib.card_cache_correct.argtypes = [_P, _i32p, C.c_int32]
+    lib.card_cache_epoch.restype = C.c_int64
+    lib.card_cache_epoch.argtypes = [_P]
+    lib.card_cache_depth.restype = C.c_int32
+    lib.card_cache_depth.argtypes = [_P]
+    lib.card_cache_read_level.restype = C.c_int
+    lib.card_cache_read_level.argtypes = [_P, C.c_int32, _i32p, _i32p, _f32p]
+    return lib
+
+
+class _Library:
+    """libcard.so, opened at the first use of any entry point (so that the build step can import
+    this package before the library exists).  There is no other implementation behind it: a
+    missing library raises ImportError at that first use."""
+
+    def __init__(self):
+        self._cdll = None
+
+    def __getattr__(self, name):
+        if self._cdll is None:
+            self._cdll = _declare(_load())
+        return getattr(self._cdll, name)
+
+
+lib = _Library()
 
 
 def _ptr(x) -> Optional[int]:
@@ -156,6 +179,14 @@ def card_kv_gather(cfg, kv: CardKV, layer: int, first_slot: int, count: int, k_o
 
 def card_profile_enable(max_launches: int) -> int:
     return lib.card_profile_enable(max_launches)
+
+
+def card_profile_disable() -> int:
+    return lib.card_profile_disable()
+
+
+def card_workspace_init(cfg, workspace_dev, stream=None) -> int:
+    return lib.card_workspace_init(C.byref(cfg), _ptr(workspace_dev), _ptr(stream))
 
 
 def card_profile_timeline(buf_dev, layer: int) -> int:

@@ -1,6 +1,8 @@
 // C ABI of libcard: argument checks and the launch sequence of one verification step.
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
+#include <mutex>
 #include <hip/hip_runtime.h>
 
 #include <vector>
@@ -20,54 +22,93 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? CARD_OK : 
 unsigned long long* g_ts_buf = nullptr;
 int g_ts_layer = 0;
 
-// benchmark hook: event pairs around the verify kernel
+// Benchmark hook: event pairs around the verify kernel.  One user at a time (the lock only keeps
+// enable / disable / collect and a concurrent card_verify from tearing the vectors).  The events
+// are destroyed by card_profile_disable, never by a static destructor: at process exit the HIP
+// runtime may already be gone.
 struct Profile {
-    bool on = false;
+    std::mutex mu;
+    std::atomic<bool> on{false};
     int used = 0;
     std::vector<hipEvent_t> start, stop;
 };
-Profile g_prof;
+Profile& prof() {
+    static Profile* p = new Profile;  // leaked on purpose: no destructor runs after HIP teardown
+    return *p;
+}
 
 struct ProfScope {
     hipStream_t st;
-    int idx = -1;
+    hipEvent_t stop = nullptr;
     explicit ProfScope(hipStream_t s) : st(s) {
-        if (g_prof.on && g_prof.used < int(g_prof.start.size())) {
-            idx = g_prof.used++;
-            (void)hipEventRecord(g_prof.start[idx], st);
+        Profile& p = prof();
+        if (!p.on) return;
+        std::lock_guard<std::mutex> g(p.mu);
+        if (p.on && p.used < int(p.start.size())) {
+            const int idx = p.used++;
+            (void)hipEventRecord(p.start[idx], st);
+            stop = p.stop[idx];
         }
     }
     ~ProfScope() {
-        if (idx >= 0) (void)hipEventRecord(g_prof.stop[idx], st);
+        if (stop) (void)hipEventRecord(stop, st);
     }
 };
 
+constexpr int kMaxDevices = 64;
+
+// Compute units of the current device (cached per device id).
 int cu_count() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 0;
+    static std::atomic<int> cus[kMaxDevices];
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    n = cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-        cus = n;
+        cus[dev].store(n, std::memory_order_relaxed);
     }
-    return cus;
+    return n;
 }
 
-// Workgroups of the verify kernel: one per compute unit, at most 256 (the barrier polls 256 flags).
-int grid_size() {
+// Workgroups of the verify kernel: cfg->grid_wgs if the caller fixed it, else one per compute
+// unit; at most 256 (the barrier polls 256 flags), never more than the compute units there are
+// (every workgroup needs a compute unit of its own: the grid meets at barriers).
+int grid_size(const card_model_cfg* cfg) {
     const int cus = cu_count();
-    return cus > 256 ? 256 : cus;
+    int n = cus > 256 ? 256 : cus;
+    if (cfg && cfg->grid_wgs > 0) {
+        if (cfg->grid_wgs > n) return 0;
+        n = cfg->grid_wgs;
+    }
+    return n;
 }
 
+// The kernel synchronises its workgroups through flags in memory, so all of them have to be
+// resident at once.  It is launched as an ordinary kernel: one workgroup fills a compute unit
+// (158.5 KiB of its LDS, 512 threads with 256 registers each), the grid is no larger than the
+// number of compute units, and the occupancy query below confirms that the device can hold a
+// workgroup per compute unit, so on an otherwise idle device the dispatcher places all of them.
+// Should other work hold compute units for longer than the kernel's bounded waits, the step ends
+// with accepted_len = -1 instead of hanging.
 template <int MT, int H, bool PK>
 int launch_mega(MegaArgs& a, hipStream_t st) {
-    void* params[] = {&a};
-    const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<void*>(k_verify<MT, H, PK>), dim3(a.nwg),
-                                                    dim3(kBlockThreads), params, 0, st);
-    return e == hipSuccess ? CARD_OK : CARD_EDEVICE;
+    static std::atomic<int> fits[kMaxDevices];  // 0 unknown, 1 yes, -1 no
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CARD_EDEVICE;
+    int f = fits[dev].load(std::memory_order_relaxed);
+    if (f == 0) {
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify<MT, H, PK>, kBlockThreads, 0) != hipSuccess)
+            return CARD_EDEVICE;
+        f = per_cu >= 1 ? 1 : -1;
+        fits[dev].store(f, std::memory_order_relaxed);
+    }
+    if (f < 0 || a.nwg > cu_count()) return CARD_EDEVICE;
+    hipLaunchKernelGGL((k_verify<MT, H, PK>), dim3(a.nwg), dim3(kBlockThreads), 0, st, a);
+    return launch_status();
 }
 
-// One persistent cooperative kernel runs the whole step (card_verify.hip).
+// One persistent kernel runs the whole step (card_verify.hip).
 int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv, int32_t ctx_len,
                 const int32_t* cand, int32_t r, void* workspace, void* stream, card_verify_result* out,
                 int32_t* row_argmax, float* logits) {
@@ -75,10 +116,12 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     const Layout L = make_layout(cfg);
     if (!L.ok) return CARD_EINVAL;
     if (!kv->k_pages || !kv->v_pages || !kv->block_table || kv->n_pages <= 0) return CARD_EINVAL;
+    // one layer of a page pool is addressed with 32-bit byte offsets
+    if (size_t(kv->n_pages) * cfg->n_kv_heads * 16 * cfg->head_dim * 2 >= (size_t(1) << 32)) return CARD_EINVAL;
     if (r < 1 || r > cfg->max_r) return CARD_ERANGE;
     if (ctx_len < 0) return CARD_EINVAL;
     if (int64_t(ctx_len) + r > cfg->max_ctx) return CARD_ECAPACITY;
-    const int cus = grid_size();
+    const int cus = grid_size(cfg);
     if (cus <= 0) return CARD_EDEVICE;
 
     char* ws = static_cast<char*>(workspace);
@@ -227,7 +270,7 @@ int card_weights_pack_tensor(const card_model_cfg* cfg, int32_t tensor, int32_t 
         a.head_dim = h;
         a.Nt = m.Nt;
         a.NB = m.NB;
-        a.nwg = grid_size();
+        a.nwg = grid_size(cfg);
         if (a.nwg <= 0) return int(CARD_EDEVICE);
         // whoever verifies with these weights must run the grid they were laid out for
         if (hipMemsetD32Async(reinterpret_cast<hipDeviceptr_t>(pb + L.stamp_off), int(kStampMagic), 1, st) != hipSuccess ||
@@ -281,28 +324,62 @@ int card_profile_timeline(void* buf_dev, int32_t layer) {
 
 int card_profile_enable(int32_t max_launches) {
     if (max_launches <= 0) return CARD_EINVAL;
-    while (int(g_prof.start.size()) < max_launches) {
+    Profile& p = prof();
+    std::lock_guard<std::mutex> g(p.mu);
+    while (int(p.start.size()) < max_launches) {
         hipEvent_t a, b;
-        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return CARD_EDEVICE;
-        g_prof.start.push_back(a);
-        g_prof.stop.push_back(b);
+        if (hipEventCreate(&a) != hipSuccess) return CARD_EDEVICE;
+        if (hipEventCreate(&b) != hipSuccess) {
+            (void)hipEventDestroy(a);
+            return CARD_EDEVICE;
+        }
+        p.start.push_back(a);
+        p.stop.push_back(b);
     }
-    g_prof.on = true;
-    g_prof.used = 0;
+    p.used = 0;
+    p.on = true;
     return CARD_OK;
 }
 
 int card_profile_collect(float* ms_host, int32_t* n_host) {
     if (!ms_host || !n_host) return CARD_EINVAL;
-    const int n = g_prof.used;
-    g_prof.on = false;
-    g_prof.used = 0;
+    Profile& p = prof();
+    std::lock_guard<std::mutex> g(p.mu);
+    const int n = p.used;
+    p.on = false;
+    p.used = 0;
     for (int i = 0; i < n; ++i) {
-        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) return CARD_EDEVICE;
-        if (hipEventElapsedTime(&ms_host[i], g_prof.start[i], g_prof.stop[i]) != hipSuccess) return CARD_EDEVICE;
+        if (hipEventSynchronize(p.stop[i]) != hipSuccess) return CARD_EDEVICE;
+        if (hipEventElapsedTime(&ms_host[i], p.start[i], p.stop[i]) != hipSuccess) return CARD_EDEVICE;
     }
     *n_host = n;
     return CARD_OK;
+}
+
+int card_profile_disable(void) {
+    Profile& p = prof();
+    std::lock_guard<std::mutex> g(p.mu);
+    p.on = false;
+    p.used = 0;
+    int st = CARD_OK;
+    for (hipEvent_t e : p.start)
+        if (hipEventDestroy(e) != hipSuccess) st = CARD_EDEVICE;
+    for (hipEvent_t e : p.stop)
+        if (hipEventDestroy(e) != hipSuccess) st = CARD_EDEVICE;
+    p.start.clear();
+    p.stop.clear();
+    return st;
+}
+
+int card_workspace_init(const card_model_cfg* cfg, void* workspace_dev, void* stream) {
+    if (!workspace_dev) return CARD_EINVAL;
+    const Layout L = make_layout(cfg);
+    if (!L.ok) return CARD_EINVAL;
+    char* ws = static_cast<char*>(workspace_dev);
+    if (reinterpret_cast<uintptr_t>(ws) % 16 || L.ws_bytes % 16) return CARD_EINVAL;
+    hipLaunchKernelGGL(k_ws_init, dim3(1024), dim3(256), 0, as_stream(stream), reinterpret_cast<uint4v*>(ws),
+                       L.ws_bytes / 16, reinterpret_cast<uint32_t*>(ws + L.m_bar_off) + kBarMagic);
+    return launch_status();
 }
 
 int card_kv_gather(const card_model_cfg* cfg, const card_kv* kv, int32_t layer, int32_t first_slot, int32_t count,

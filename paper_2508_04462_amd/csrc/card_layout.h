@@ -16,6 +16,9 @@ constexpr int kKvBlock = 16;
 constexpr int kNbQkv = 2, kNbOne = 1, kNbWide = 8;
 constexpr int kFlagCopies = 32;  // copies of the barrier flags (256 words each): pollers spread over them
 constexpr uint32_t kStampMagic = 0x43415244u;  // "CARD"
+constexpr uint32_t kWsMagic = 0x57534b31u;     // workspace control words initialised ("WSK1"), word kBarMagic
+// words of the barrier block: [1] exit counter, [2] error flag, [3] barrier epoch, [4] magic
+constexpr int kBarExit = 1, kBarError = 2, kBarEpoch = 3, kBarMagic = 4;
 
 #ifdef __HIPCC__
 #define CARD_HD __host__ __device__
@@ -105,6 +108,7 @@ inline bool cfg_valid(const card_model_cfg* c) {
     if (c->max_ctx <= 0 || c->max_ctx % kKvBlock) return false;
     if (c->max_r < 1 || c->max_r > kMaxR) return false;
     if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return false;
+    if (c->grid_wgs < 0 || c->grid_wgs > 256) return false;
     return true;
 }
 
@@ -138,6 +142,10 @@ inline Layout make_layout(const card_model_cfg* c) {
     lo = align_up(lo + size_t(d) * 4, 1024);
     L.layer_stride = lo;
     L.weight_bytes = L.layer0_off + size_t(c->n_layers) * L.layer_stride;
+    // the kernel addresses a matrix with 32-bit byte offsets
+    constexpr size_t k4G = size_t(1) << 32;
+    if (L.qkv.bytes() >= k4G || L.wo.bytes() >= k4G || L.gu.bytes() >= k4G || L.wd.bytes() >= k4G || L.lm.bytes() >= k4G)
+        return L;
 
     // workspace
     size_t w = 0;

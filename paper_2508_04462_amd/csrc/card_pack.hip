@@ -45,6 +45,17 @@ __global__ __launch_bounds__(256) void k_pack(PackArgs a) {
     reinterpret_cast<bf16x8*>(a.dst)[size_t(stream_frag_index(a.Nt, a.Ks, a.NB, a.nwg, t, s)) * 64 + lane] = v;
 }
 
+// A workspace is prepared by clearing all of it (control words must start at zero; the kernel
+// multiplies hand-over bytes it never wrote - rows beyond r, k-steps beyond a wavefront's share
+// - with zero weights, so those bytes have to be finite) and setting the mark that says so.
+__global__ __launch_bounds__(256) void k_ws_init(uint4v* ws, size_t n16, uint32_t* magic_word) {
+    const size_t stride = size_t(gridDim.x) * 256;
+    for (size_t i = size_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride) ws[i] = uint4v{0u, 0u, 0u, 0u};
+    // the mark lives in a 16-byte unit that this same thread has just cleared
+    const size_t mi = size_t(reinterpret_cast<char*>(magic_word) - reinterpret_cast<char*>(ws)) / 16;
+    if (mi % stride == size_t(blockIdx.x) * 256 + threadIdx.x) *magic_word = kWsMagic;
+}
+
 struct GatherArgs {
     const __bf16* kpool;
     const __bf16* vpool;

@@ -72,7 +72,7 @@ struct MegaArgs {
     size_t xfrag_stride, attfrag_stride, actfrag_stride, qfrag_stride;
     float* rope;
     unsigned long long* best;
-    uint32_t* bar;     // [1] exit counter, [2] error flag (zero between calls), [3] barrier epoch
+    uint32_t* bar;     // kBarExit, kBarError (zero between calls), kBarEpoch, kBarMagic
     uint32_t* flags;   // [kFlagCopies][256] last barrier sequence number each workgroup has reached
     uint32_t* acount;  // [Hkv * row_tiles] arrival counters of the attention cuts; zero between uses
     const int32_t* cand;
@@ -100,6 +100,7 @@ struct __align__(16) MegaSmem {
     uint32_t head[kMegaWaves];   // fragments popped so far (written by the consumer)
     uint32_t cbar;               // arrivals at the consumer barrier (monotonic)
     int failed;
+    int ws_ok;
     uint32_t epoch;
     int pred[kMaxR + 1];
 };
@@ -191,7 +192,7 @@ __device__ __forceinline__ void grid_wait(const MegaArgs& a, uint32_t& gen, Mega
     cbar(sm, cgen);
     gen += 1;
     if (threadIdx.x == 0 && sm.failed) {  // a bounded wait ran out in this workgroup: tell the one that reports
-        __hip_atomic_store(&a.bar[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&a.bar[kBarError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
     }
     if (threadIdx.x < 64 && !sm.failed) {
@@ -214,7 +215,7 @@ __device__ __forceinline__ void grid_wait(const MegaArgs& a, uint32_t& gen, Mega
             if (++spins > kSpinLimit) {
                 if (lane == 0) {
                     sm.failed = 1;
-                    __hip_atomic_store(&a.bar[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&a.bar[kBarError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
                 break;
             }
@@ -792,6 +793,27 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                             q += 1;
                         }
                     }
+                    // a page is opened by the call that writes its first slot: clear the slots behind
+                    // the ones written, so that a later step never multiplies a zero probability with
+                    // bits nobody stored (0 x NaN)
+                    if (tk == 0) {
+                        int t = run;
+                        while (t < 16) {
+                            __bf16* dst = ea.vpool + vb + v_page_index(jg, t);
+                            if ((t & 3) == 0) {
+                                __hip_atomic_store(reinterpret_cast<unsigned long long*>(dst), 0ull, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                                t += 4;
+                            } else if ((t & 1) == 0) {
+                                __hip_atomic_store(reinterpret_cast<uint32_t*>(dst), 0u, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                                t += 2;
+                            } else {
+                                st_dev_bf16(dst, static_cast<__bf16>(0.f));
+                                t += 1;
+                            }
+                        }
+                    }
                     m2 += run;
                 }
             }
@@ -1191,11 +1213,23 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
     if (tid == 0) {
         sm.failed = 0;
         sm.cbar = 0;
-        sm.epoch = __hip_atomic_load(&a.bar[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm.epoch = __hip_atomic_load(&a.bar[kBarEpoch], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm.ws_ok = __hip_atomic_load(&a.bar[kBarMagic], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == kWsMagic;
     }
     if (tid < kMegaWaves) sm.tail[tid] = sm.head[tid] = 0;
     if (tid < kMaxR) sm.wg_best[tid] = 0ull;
     __syncthreads();  // the only hardware barrier: producers and consumers part ways here
+    // A workspace whose control words were never prepared could hold flags that let barriers fall
+    // through: every workgroup reads the same word, so all of them leave, and the step fails.
+    if (!sm.ws_ok) {
+        if (wg == 0 && tid == 0) {
+            a.out->accepted_len = -1;
+            a.out->correction_token = -1;
+            a.out->kv_first_slot = a.ctx_len;
+            a.out->kv_count = 0;
+        }
+        return;
+    }
 
     if (wave >= kMegaWaves) {
         producer(a, sm, wave - kMegaWaves, lane, wg);
@@ -1363,8 +1397,11 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
             while (j < a.r && a.cand[j] == sm.pred[j]) ++j;
             // weights laid out for another grid size would stream in the wrong order
             const bool bad_layout = a.stamp[0] != kStampMagic || a.stamp[1] != uint32_t(nwg);
-            const bool failed = bad_layout || sm.failed ||
-                                __hip_atomic_load(&a.bar[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+            // a token id outside the vocabulary was clamped by the embedding gather: the step is void
+            bool bad_token = false;
+            for (int i = 0; i < a.r; ++i) bad_token = bad_token || a.cand[i] < 0 || a.cand[i] >= a.V;
+            const bool failed = bad_layout || bad_token || sm.failed ||
+                                __hip_atomic_load(&a.bar[kBarError], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
             a.out->accepted_len = failed ? -1 : j;
             a.out->correction_token = failed ? -1 : sm.pred[j];
             a.out->kv_first_slot = a.ctx_len;
@@ -1374,12 +1411,12 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
     }
     // the last workgroup to leave re-arms the counters for the next call
     if (tid == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(&a.bar[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = __hip_atomic_fetch_add(&a.bar[kBarExit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (prev == uint32_t(nwg) - 1) {
             // barrier sequence numbers of the next call start above anything this call used
-            __hip_atomic_store(&a.bar[3], sm.epoch + 8192u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&a.bar[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&a.bar[2], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.bar[kBarEpoch], sm.epoch + 8192u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.bar[kBarExit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.bar[kBarError], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }

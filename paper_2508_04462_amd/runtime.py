@@ -8,11 +8,11 @@ import torch
 from . import binding as B
 
 
-def make_cfg(shape, max_ctx: int, max_r: int = 32) -> B.CardModelCfg:
+def make_cfg(shape, max_ctx: int, max_r: int = 32, grid_wgs: int = 0) -> B.CardModelCfg:
     """shape: any object with the ModelShape fields."""
     max_ctx = (max_ctx + 15) // 16 * 16
     return B.CardModelCfg(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
-                          shape.d_ffn, shape.vocab, shape.rope_theta, shape.rms_eps, 16, max_ctx, max_r)
+                          shape.d_ffn, shape.vocab, shape.rope_theta, shape.rms_eps, 16, max_ctx, max_r, grid_wgs)
 
 
 def _check(st: int, where: str) -> None:
@@ -24,20 +24,26 @@ class Target:
     """The target model's device state: packed weights, workspace, paged KV cache."""
 
     def __init__(self, shape, max_ctx: int, max_r: int = 32, device: str = "cuda:0",
-                 page_order: Optional[Sequence[int]] = None):
+                 page_order: Optional[Sequence[int]] = None, grid_wgs: int = 0, pool_fill: Optional[int] = None):
+        """pool_fill: byte value the KV page pools start with (tests; None = whatever torch.empty
+        hands out)."""
         if not torch.cuda.is_available():
             raise RuntimeError("libcard needs a GPU: there is no CPU path")
         self.device = torch.device(device)
-        self.cfg = make_cfg(shape, max_ctx, max_r)
+        self.cfg = make_cfg(shape, max_ctx, max_r, grid_wgs)
         wbytes = B.card_packed_weight_bytes(self.cfg)
         if wbytes == 0:
             raise B.CardError(B.CARD_EINVAL, "card_packed_weight_bytes")
         self.packed = torch.empty(wbytes, dtype=torch.uint8, device=self.device)
-        self.workspace = torch.zeros(B.card_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(B.card_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        _check(B.card_workspace_init(self.cfg, self.workspace, self._stream()), "card_workspace_init")
         self.n_pages = self.cfg.max_ctx // 16
         pool = B.card_kv_pool_bytes(self.cfg, self.n_pages)
-        self.k_pages = torch.zeros(pool, dtype=torch.uint8, device=self.device)
-        self.v_pages = torch.zeros(pool, dtype=torch.uint8, device=self.device)
+        self.k_pages = torch.empty(pool, dtype=torch.uint8, device=self.device)
+        self.v_pages = torch.empty(pool, dtype=torch.uint8, device=self.device)
+        if pool_fill is not None:
+            self.k_pages.fill_(pool_fill)
+            self.v_pages.fill_(pool_fill)
         order = list(range(self.n_pages)) if page_order is None else [int(p) for p in page_order]
         assert sorted(order) == list(range(self.n_pages))
         self.block_table = torch.tensor(order, dtype=torch.int32, device=self.device)

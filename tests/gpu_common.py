@@ -16,12 +16,13 @@ def shuffled_pages(n_pages: int, seed: int):
     return [int(p) for p in order]
 
 
-def make_pair(shape, seed, max_ctx, gain_jitter=0.0, dtype=np.float64, shuffle=True, max_r=32):
+def make_pair(shape, seed, max_ctx, gain_jitter=0.0, dtype=np.float64, shuffle=True, max_r=32, pool_fill=None):
     import paper_2508_04462_amd as card
     from paper_2508_04462_amd.synthetic import load_synthetic_weights
 
     n_pages = (max_ctx + 15) // 16
-    tgt = card.Target(shape, max_ctx, max_r=max_r, page_order=shuffled_pages(n_pages, seed) if shuffle else None)
+    tgt = card.Target(shape, max_ctx, max_r=max_r, page_order=shuffled_pages(n_pages, seed) if shuffle else None,
+                      pool_fill=pool_fill)
     load_synthetic_weights(tgt, shape, seed, gain_jitter)
     w = oracle_weights(shape, seed, gain_jitter, dtype=dtype)
     return tgt, w

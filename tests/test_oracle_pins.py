@@ -300,3 +300,31 @@ def test_chained_verify_reproduces_greedy_stream_for_any_candidate_quality():
         pending = res.correction_token
         step += 1
     assert emitted[:12] == want
+
+
+@pytest.mark.parametrize("store", ["bf16", "exact"])
+@pytest.mark.parametrize("seed", [3, 6])
+def test_greedy_decode_cached_equals_bruteforce_and_its_gaps_are_the_recomputed_rows(store, seed):
+    """The cached decoder writes the greedy stream and the gaps of every stored golden and of
+    most GPU cases.  Pinned against the cache-free path: the stream equals brute-force decoding
+    (whole sequence recomputed per token) and gap i is the top-1/top-2 distance of the row of
+    `full_recompute` that predicts token i+1.  A shifted position, a stale cache row or a gap
+    taken from the wrong row fails here."""
+    cfg = ODD
+    w = oracle_weights(cfg, seed, gain_jitter=0.2)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, cfg.ctx, cfg.vocab).tolist()
+    n_new = 7
+    kv = co.OracleKV.empty(cfg, 32, store=store)
+    g0 = co.prefill(cfg, w, kv, ctx, chunk=4)
+    toks, gaps = co.greedy_decode_cached(cfg, w, kv, cfg.ctx, g0, n_new)
+    assert len(toks) == n_new + 1 and len(gaps) == n_new and toks[0] == g0
+    assert toks == co.greedy_decode_bruteforce(cfg, w, ctx, n_new + 1, store=store)
+    full = co.full_recompute(cfg, w, ctx + toks[:-1], store=store)
+    for i in range(n_new):  # the row at position ctx + i was fed toks[i] and predicts toks[i + 1]
+        row = full[cfg.ctx + i]
+        assert co.argmax_lowest(row) == toks[i + 1]
+        assert abs(co.top2_gap(row) - gaps[i]) < 1e-9
+    # the cache now holds the stream's keys: a further row sees exactly the recomputed history
+    nxt = co.forward_rows(cfg, w, kv, [toks[-1]], cfg.ctx + n_new)[0]
+    ref = co.full_recompute(cfg, w, ctx + toks, store=store)[-1]
+    np.testing.assert_allclose(nxt, ref, rtol=1e-10, atol=1e-12)
