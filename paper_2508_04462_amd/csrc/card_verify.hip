@@ -367,11 +367,13 @@ struct FifoC {
     uint32_t head, tail_seen;  // in fragments
     uint32_t pos;              // slot of the next fragment
     bool dead;
+    uint32_t waited;           // 100 MHz ticks spent waiting for fragments (read by the phase timeline)
 };
 
 // Wait until `need` fragments are there.
 __device__ __forceinline__ void fifo_wait(MegaSmem& sm, FifoC& f, int w, uint32_t need) {
     if (__builtin_expect(f.tail_seen - f.head >= need, 1)) return;
+    const unsigned long long w0 = wall_clock64();
     uint32_t spins = 0;
     while (!f.dead) {
         f.tail_seen = lds_peek(&sm.tail[w]);
@@ -382,6 +384,7 @@ __device__ __forceinline__ void fifo_wait(MegaSmem& sm, FifoC& f, int w, uint32_
             lds_post(reinterpret_cast<uint32_t*>(&sm.failed), 1u);
         }
     }
+    f.waited += uint32_t(wall_clock64() - w0);
     asm volatile("" ::: "memory");
 }
 
@@ -389,6 +392,7 @@ enum MegaEpi { ME_QKV = 0, ME_RESID = 1, ME_SWIGLU = 2, ME_LM = 3 };
 
 struct EpiArgs {
     int32_t layer;
+    int32_t ts0;  // timeline slots of this phase: ts0 first activations in, ts0+1 k-loop left, ts0+2 ticks spent waiting for fragments; <= 0: none
     const float* ss_in;      // [32 rows][d/16] partial sums of squares of the input rows (norm phases)
     // RESID
     const float* xres_old;
@@ -521,6 +525,12 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
     }
 
     bool hook_done = false;
+    const uint32_t waited0 = fc.waited;
+    const bool gts = a.ts && ea.ts0 > 0 && ea.layer == a.ts_layer && tid == 0;
+    if (gts) {
+        asm volatile("" ::"v"(xh[0][0]));  // the first activations have arrived
+        a.ts[size_t(blockIdx.x) * 32 + ea.ts0] = wall_clock64();
+    }
 
     for (int b = 0; b < n_batches; ++b) {
         floatx4 acc[NB][MT];
@@ -586,6 +596,10 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
             }
         }
         if (b + 1 == n_batches) {
+            if (gts) {
+                a.ts[size_t(blockIdx.x) * 32 + ea.ts0 + 1] = wall_clock64();
+                a.ts[size_t(blockIdx.x) * 32 + ea.ts0 + 2] = fc.waited - waited0;
+            }
             after_k();
             hook_done = true;
         }
@@ -1237,7 +1251,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
     }
 
     uint32_t gen = 0, cgen = 0;
-    FifoC fc = {0u, 0u, 0u, false};
+    FifoC fc = {0u, 0u, 0u, false, 0u};
     const int n_dt = a.d >> 4;  // 16-column tiles of the residual stream
     auto layer_base = [&](int l) { return a.wbase + a.layer0_off + size_t(l) * a.layer_stride; };
 
@@ -1318,6 +1332,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
             CARD_TS(16)
         };
         CARD_TS(0)
+        ea.ts0 = 21;
         gemm_phase<kNbQkv, MT, ME_QKV, PK>(a, p_qkv, a.xfrag + v0 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea, fc,
                                           sm, wave, lane, cgen, preload);
         CARD_TS(1)
@@ -1338,6 +1353,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         ea.xfrag_new = a.xfrag + v1 * a.xfrag_stride;
         ea.ss_new = a.ss + v1 * ss_stride;
         ea.gain_next = reinterpret_cast<const float*>(lb + a.g_ffn_off);
+        ea.ts0 = 24;
         gemm_phase<kNbOne, MT, ME_RESID, PK>(a, p_wo, a.attfrag + size_t(l) * a.attfrag_stride,
                                             uint32_t(a.attfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
         CARD_TS(5)
@@ -1349,6 +1365,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         const PhasePlan p_gu = stream_phase(a, 4 * l + SP_GU, wg, wave);
         ea.ss_in = a.ss + v1 * ss_stride;
         ea.actfrag = a.actfrag + size_t(l) * a.actfrag_stride;
+        ea.ts0 = 0;
         gemm_phase<kNbWide, MT, ME_SWIGLU, PK>(a, p_gu, a.xfrag + v1 * a.xfrag_stride, uint32_t(a.xfrag_stride * 2), ea,
                                               fc, sm, wave, lane, cgen);
         CARD_TS(7)
@@ -1364,6 +1381,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         ea.ss_new = a.ss + v2 * ss_stride;
         ea.gain_next = last ? reinterpret_cast<const float*>(a.wbase + a.g_final_off)
                             : reinterpret_cast<const float*>(layer_base(l + 1) + a.g_attn_off);
+        ea.ts0 = 27;
         gemm_phase<kNbOne, MT, ME_RESID, PK>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride,
                                             uint32_t(a.actfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
         CARD_TS(9)

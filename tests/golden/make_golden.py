@@ -99,7 +99,15 @@ def main():
     kv = co.OracleKV.empty(shape, n_ctx + n_new + r + 8, dt)
     g0 = co.prefill(shape, w, kv, ctx, dt, chunk=128)
     print(f"prefill done {time.time() - t0:.0f}s g0={g0}", flush=True)
-    greedy, gaps = co.greedy_decode_cached(shape, w, kv, n_ctx, g0, n_new, dt)
+    # decode in pieces of r tokens and stop at the first fully decisive run of r rows
+    greedy, gaps = [g0], []
+    while len(gaps) < n_new:
+        more, mg = co.greedy_decode_cached(shape, w, kv, n_ctx + len(gaps), greedy[-1], min(r, n_new - len(gaps)), dt)
+        greedy += more[1:]
+        gaps += mg
+        if args.window and len(gaps) >= r and any(all(g > GAP for g in gaps[k: k + r]) for k in range(len(gaps) - r + 1)):
+            break
+    n_new = len(gaps)
     print(f"greedy {greedy} gaps {gaps} {time.time() - t0:.0f}s", flush=True)
     rng = np.random.default_rng(1234)
     sample_idx = sorted(set(rng.integers(0, shape.vocab, size=48).tolist() + [int(t) for t in greedy[: r + 1]]))

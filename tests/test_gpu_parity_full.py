@@ -42,7 +42,8 @@ def _run(golden_name, logit_tol=LOGIT_TOL):
     with open(os.path.join(GOLDEN, golden_name)) as f:
         g = json.load(f)
     shape, seed, ctx_len, r = ci.SHAPES[g["shape"]], g["seed"], g["ctx"], g["r"]
-    max_ctx = (ctx_len + 2 * r + 8 + 15) // 16 * 16
+    extra = len(g["window"]["extra_ctx"]) if "window" in g else 0
+    max_ctx = (ctx_len + extra + 2 * r + 8 + 15) // 16 * 16
     tgt = card.Target(shape, max_ctx, page_order=shuffled_pages(max_ctx // 16, seed))
     load_synthetic_weights(tgt, shape, seed)
     ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, ctx_len, shape.vocab).tolist()
@@ -78,11 +79,35 @@ def _run(golden_name, logit_tol=LOGIT_TOL):
         assert np.all(np.abs(np.abs(full).max(axis=1) - np.asarray(case["row_absmax"])) / np.asarray(case["row_absmax"])
                       <= logit_tol)
     assert checked_rows > 0
+    _window_case(tgt, g, ctx, logit_tol)
     return g
 
 
+def _window_case(tgt, g, ctx, logit_tol):
+    """The stored fully decisive step (make_golden.py --window): the context is followed by the
+    oracle's own greedy tokens up to a point where r rows in a row have a top-1/top-2 gap above
+    0.05; the candidates are the next r greedy tokens, so the step is accepted in full and the
+    HIP path has to give accepted_len = r and the oracle's correction token bit-exactly."""
+    w = g.get("window")
+    if w is None:
+        return
+    r, n = g["r"], w["ctx_len"]
+    assert n == g["ctx"] + len(w["extra_ctx"]) and all(gap > GAP for gap in w["row_gap"])
+    assert w["accepted_len"] == r and w["cand"][0] == w["pending"]
+    tgt.prefill(list(ctx) + w["extra_ctx"])
+    res = tgt.verify(n, w["pending"], w["cand"], want_logits=True)
+    assert res["row_argmax"] == w["row_argmax"]
+    assert (res["accepted_len"], res["correction_token"]) == (r, w["correction_token"])
+    assert (res["kv_first_slot"], res["kv_count"]) == (n, r)
+    got = res["logits"][:, w["sample_idx"]].double().numpy()
+    ref = np.asarray(w["logit_sample"], dtype=np.float64)
+    err = np.abs(got - ref).max(axis=1) / np.asarray(w["row_absmax"])
+    assert err.max() <= logit_tol, err.tolist()
+
+
 def test_tiny_against_stored_oracle_values():
-    _run("tiny_seed1.json")
+    g = _run("tiny_seed1.json")
+    assert g["kv_store"] == "bf16" and "window" in g
 
 
 FULL = sorted(f for f in os.listdir(GOLDEN) if f.startswith("llama8b_seed") and f.endswith(".json"))
@@ -93,5 +118,5 @@ def test_full_size_workload_against_stored_oracle_values(golden_name):
     """The configuration bench.py times: 8B shape, 1024 tokens of context, r = 8, one workgroup
     per compute unit; planted prefixes j = 0, 4, 8; one case per stored seed."""
     g = _run(golden_name, LOGIT_TOL_FULL)
-    assert g["shape"] == "llama8b" and g["ctx"] == 1024 and g["r"] == 8 and g.get("kv_store", "bf16") == "bf16"
+    assert g["shape"] == "llama8b" and g["ctx"] == 1024 and g["r"] == 8 and g["kv_store"] == "bf16"
     torch.cuda.synchronize()

@@ -328,3 +328,4 @@ def test_greedy_decode_cached_equals_bruteforce_and_its_gaps_are_the_recomputed_
     nxt = co.forward_rows(cfg, w, kv, [toks[-1]], cfg.ctx + n_new)[0]
     ref = co.full_recompute(cfg, w, ctx + toks, store=store)[-1]
     np.testing.assert_allclose(nxt, ref, rtol=1e-10, atol=1e-12)
+
