@@ -37,7 +37,8 @@ typedef enum card_status {
     CARD_ERANGE = -2,    /* r outside [1, max_r], level / index outside the cache         */
     CARD_ECAPACITY = -3, /* ctx_len + r exceeds max_ctx or the block table                 */
     CARD_EDEVICE = -4,   /* a HIP call failed (launch error, wrong device architecture)    */
-    CARD_ESTALE = -5     /* cache write refers to an epoch that a correction has ended     */
+    CARD_ESTALE = -5,    /* cache write refers to an epoch that a correction has ended     */
+    CARD_ETOOBIG = -6    /* card_verify_static: the model's workspace exceeds the scratch   */
 } card_status;
 
 const char* card_strerror(int status);
@@ -172,6 +173,25 @@ typedef struct card_verify_result {
 int card_verify(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
                 int32_t ctx_len, const int32_t* cand_tokens_dev, int32_t r, void* workspace_dev,
                 void* stream, card_verify_result* out_dev, int32_t* row_argmax_dev);
+
+/* card_verify for callers that cannot allocate device memory or hand a workspace over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same step, same
+ * results; the workspace is a 32 MiB array that lives in the library's code object (each GPU the
+ * library runs on holds its own copy until the process ends), so the call allocates nothing and
+ * takes no workspace argument.  Limits and rules:
+ *   - card_workspace_bytes(cfg) must not exceed card_static_scratch_bytes() (32 MiB: models up to
+ *     a few layers of width 512 at max_r 32), else CARD_ETOOBIG and nothing is enqueued;
+ *   - every call on a GPU shares that GPU's array, which keeps the last call's contents: the
+ *     first call, and a call for another cfg than the previous one, clear the part they use
+ *     (a small kernel on `stream`, in front of the step); calls that overlap on one GPU race;
+ *   - after a call that reported accepted_len < 0 call card_static_scratch_reset(): the next
+ *     call on the current device then clears the array again before it runs.
+ * Inputs and outputs are the caller's, as for card_verify. */
+int card_verify_static(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
+                       int32_t ctx_len, const int32_t* cand_tokens_dev, int32_t r, void* stream,
+                       card_verify_result* out_dev, int32_t* row_argmax_dev);
+size_t card_static_scratch_bytes(void);
+int card_static_scratch_reset(void);
 
 /* Test entry point, not on the timed path: the same forward, additionally storing the fp32
  * logits [r][vocab] (dev) so that tests can bound the error of the final-layer logits. */

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     CARD_ECAPACITY,
     CARD_EDEVICE,
     CARD_ESTALE,
+    CARD_ETOOBIG,
     TENSOR_IDS,
     CardError,
     CardModelCfg,
@@ -28,6 +29,9 @@ from .binding import (  # noqa: F401
     card_weights_pack_tensor,
     card_verify,
     card_verify_debug_logits,
+    card_verify_static,
+    card_static_scratch_bytes,
+    card_static_scratch_reset,
     card_kv_gather,
     card_profile_enable,
     card_profile_disable,

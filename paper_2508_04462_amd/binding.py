@@ -8,7 +8,7 @@ from typing import Optional
 _PKG = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.path.join(_PKG, "libcard.so")
 
-CARD_OK, CARD_EINVAL, CARD_ERANGE, CARD_ECAPACITY, CARD_EDEVICE, CARD_ESTALE = 0, -1, -2, -3, -4, -5
+CARD_OK, CARD_EINVAL, CARD_ERANGE, CARD_ECAPACITY, CARD_EDEVICE, CARD_ESTALE, CARD_ETOOBIG = 0, -1, -2, -3, -4, -5, -6
 
 TENSOR_IDS = {
     "embed": 0, "wq": 1, "wk": 2, "wv": 3, "wo": 4, "wg": 5, "wu": 6, "wd": 7,
@@ -77,6 +77,12 @@ def _declare(lib: C.CDLL) -> C.CDLL:
     lib.card_workspace_init.argtypes = [_cfgp, _P, _P]
     lib.card_verify.restype = C.c_int
     lib.card_verify.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P]
+    lib.card_verify_static.restype = C.c_int
+    lib.card_verify_static.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P]
+    lib.card_static_scratch_bytes.restype = C.c_size_t
+    lib.card_static_scratch_bytes.argtypes = []
+    lib.card_static_scratch_reset.restype = C.c_int
+    lib.card_static_scratch_reset.argtypes = []
     lib.card_verify_debug_logits.restype = C.c_int
     lib.card_verify_debug_logits.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P, _P]
     lib.card_kv_gather.restype = C.c_int
@@ -162,6 +168,20 @@ def card_verify(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: int, wor
                 out_dev, row_argmax_dev=None) -> int:
     return lib.card_verify(C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, _ptr(cand_dev), r,
                            _ptr(workspace_dev), _ptr(stream), _ptr(out_dev), _ptr(row_argmax_dev))
+
+
+def card_verify_static(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: int, stream, out_dev,
+                       row_argmax_dev=None) -> int:
+    return lib.card_verify_static(C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, _ptr(cand_dev), r,
+                                  _ptr(stream), _ptr(out_dev), _ptr(row_argmax_dev))
+
+
+def card_static_scratch_bytes() -> int:
+    return lib.card_static_scratch_bytes()
+
+
+def card_static_scratch_reset() -> int:
+    return lib.card_static_scratch_reset()
 
 
 def card_verify_debug_logits(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: int, workspace_dev,

@@ -2,12 +2,17 @@
 #include <algorithm>
 #include <atomic>
 #include <cstdlib>
+#include <cstring>
 #include <mutex>
 #include <hip/hip_runtime.h>
 
 #include <vector>
 
 #include "card.h"
+
+#ifndef CARD_STATIC_SCRATCH_BYTES
+#define CARD_STATIC_SCRATCH_BYTES (32u << 20)
+#endif
 #include "card_pack.hip"
 #include "card_verify.hip"
 
@@ -107,6 +112,20 @@ int launch_mega(MegaArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((k_verify<MT, H, PK>), dim3(a.nwg), dim3(kBlockThreads), 0, st, a);
     return launch_status();
 }
+
+// Scratch of the entry point that allocates nothing: what card_verify takes as `workspace_dev`,
+// at a fixed place in the code object.  In host code the name is a stand-in, not a device address:
+// the address of this device's copy comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticWsBytes = size_t(CARD_STATIC_SCRATCH_BYTES);
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+
+struct StaticWs {
+    void* ptr = nullptr;       // device address of `scratch` on this device
+    bool prepared = false;     // k_ws_init has been enqueued for `cfg`'s layout
+    card_model_cfg cfg = {};
+};
+StaticWs g_static[kMaxDevices];
+std::mutex g_static_mu;
 
 // One persistent kernel runs the whole step (card_verify.hip).
 int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv, int32_t ctx_len,
@@ -215,6 +234,7 @@ const char* card_strerror(int status) {
         case CARD_ECAPACITY: return "KV cache capacity exceeded";
         case CARD_EDEVICE: return "device error";
         case CARD_ESTALE: return "stale cache epoch";
+        case CARD_ETOOBIG: return "workspace of this model exceeds the static scratch buffer";
         default: return "unknown status";
     }
 }
@@ -305,6 +325,49 @@ int card_verify(const card_model_cfg* cfg, const void* packed_weights_dev, const
                 card_verify_result* out_dev, int32_t* row_argmax_dev) {
     return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, workspace_dev, stream, out_dev,
                        row_argmax_dev, nullptr);
+}
+
+int card_verify_static(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv, int32_t ctx_len,
+                       const int32_t* cand_tokens_dev, int32_t r, void* stream, card_verify_result* out_dev,
+                       int32_t* row_argmax_dev) {
+    const Layout L = make_layout(cfg);
+    if (!L.ok) return CARD_EINVAL;
+    if (L.ws_bytes > kStaticWsBytes) return CARD_ETOOBIG;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CARD_EDEVICE;
+    void* ws = nullptr;
+    {
+        std::lock_guard<std::mutex> g(g_static_mu);
+        StaticWs& sw = g_static[dev];
+        if (!sw.ptr) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CARD_EDEVICE;
+            sw.ptr = p;
+        }
+        // The layout of the control words depends on the model: a call for another model than the
+        // last one (or the first call) clears the part it uses and sets the mark, stream-ordered in
+        // front of the step.  The array keeps the last call's contents otherwise.
+        if (!sw.prepared || memcmp(&sw.cfg, cfg, sizeof(card_model_cfg)) != 0) {
+            hipLaunchKernelGGL(k_ws_init, dim3(1024), dim3(256), 0, as_stream(stream), static_cast<uint4v*>(sw.ptr),
+                               L.ws_bytes / 16, reinterpret_cast<uint32_t*>(static_cast<char*>(sw.ptr) + L.m_bar_off) + kBarMagic);
+            if (launch_status() != CARD_OK) return CARD_EDEVICE;
+            sw.cfg = *cfg;
+            sw.prepared = true;
+        }
+        ws = sw.ptr;
+    }
+    return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, ws, stream, out_dev, row_argmax_dev,
+                       nullptr);
+}
+
+size_t card_static_scratch_bytes(void) { return kStaticWsBytes; }
+
+int card_static_scratch_reset(void) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CARD_EDEVICE;
+    std::lock_guard<std::mutex> g(g_static_mu);
+    g_static[dev].prepared = false;
+    return CARD_OK;
 }
 
 int card_verify_debug_logits(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
