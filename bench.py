@@ -8,11 +8,16 @@ tokens are resident in HBM before the timed region starts.  Candidates follow th
 recipe (first j tokens are the target's own greedy tokens, j cycling over 0..8).
 
 Prints ONE JSON line: verified tokens/s (value), latency, the HBM roofline of the dominant
-kernel measured with HIP events inside this run, and the CPU oracle timed on a bounded sample.
+kernel measured with HIP events inside this run, the CPU oracle timed on a bounded sample, and
+a `sweep` array with the other synthetic configurations (context lengths 512..32768 on the 8B
+shape, the 70B shape at r 4/8/16, the Qwen-7B shape at r 1..32 and its query / verify / correct
+loop against the shared cache at planted acceptance rates 0.3 / 0.6 / 0.9), each with latency,
+tokens/s and the fraction of the HBM roofline.
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import statistics
@@ -26,6 +31,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # the paper's end-to-end speedups are for other hardware and another metric: context only
 PAPER_CONTEXT = "CARD paper: up to 4.83x over autoregressive decoding on 3x A800-80GB, HF Transformers 4.31"
+PREFILL_MAX_CTX = 32768  # contexts beyond this would be perf-only points with noise in the cache pages
 
 
 def parse():
@@ -38,6 +44,8 @@ def parse():
     ap.add_argument("--r", type=int, default=None)
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", choices=["full", "quick", "none"], default="full",
+                    help="full: every synthetic configuration; quick: one point per kind on the headline shape; none")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a 1 GiB device copy (calibration) and 5 verify steps, no timing")
     return ap.parse_args()
@@ -51,11 +59,15 @@ def step_bytes(shape, ctx: int) -> int:
 
 
 def cpu_baseline(shape, seed: int, ctx: int, r: int, cand):
-    """The oracle as it stands, timed on the host: verify steps of the 2-layer and 4-layer
-    truncations of the workload (same widths, same context, vocabulary head included), fp32,
-    median of 10 after one warm-up (about 10 s of CPU work); the full-depth time is extrapolated
-    linearly in depth and labelled as such."""
+    """The oracle as it stands, timed on the host at FULL depth: one verify step of the workload
+    (fp32 numpy, r rows against a cache of ctx positions), median of 3 after one warm-up.  The
+    cache holds zeros instead of a prefilled context (an oracle prefill of 1024 tokens takes half
+    an hour; the step's arithmetic and memory traffic do not depend on the cached values).  If the
+    host cannot hold the fp32 weights the 2- and 4-layer truncations are timed instead and the
+    full depth is extrapolated linearly, labelled as such."""
     import numpy as np
+    import torch
+
     from oracle import card_oracle as co
     from oracle.from_inputs import oracle_weights
 
@@ -65,39 +77,262 @@ def cpu_baseline(shape, seed: int, ctx: int, r: int, cand):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    import card_inputs as ci
-    import torch
-
-    s2 = shape.with_layers(4)
     dev = "cuda:0" if torch.cuda.is_available() else "cpu"
-    w = oracle_weights(s2, seed, dtype=np.float32, device=dev)
-    ctx_tokens = ci.uniform_tokens(seed, "ctx_tokens", 0, ctx, shape.vocab).tolist()
-    kv = co.OracleKV.empty(s2, ctx + r, np.float32)
-    t0 = time.time()
-    co.prefill(s2, w, kv, ctx_tokens, np.float32, chunk=128)
-    t_prefill = time.time() - t0
 
-    def timed(cfg):
+    def timed(cfg, w, kv, n):
         ts = []
-        for i in range(11):
+        for _ in range(n + 1):
             t = time.time()
             co.verify(cfg, w, kv, ctx, -1, cand, np.float32)
             ts.append(time.time() - t)
-        return statistics.median(ts[1:])
+        return statistics.median(ts[1:]), ts[0]
 
-    t2 = timed(s2)
-    t1 = timed(shape.with_layers(2))
-    per_layer = max(t2 - t1, 0.0) / 2
-    t_full = t1 + (shape.n_layers - 2) * per_layer
+    need = 4 * (shape.n_layers * shape.weight_elems_per_layer() + 2 * shape.vocab * shape.d_model)
+    try:
+        avail = os.sysconf("SC_AVPHYS_PAGES") * os.sysconf("SC_PAGE_SIZE")
+    except (ValueError, OSError):
+        avail = 0
+    if avail > 1.6 * need:
+        t0 = time.time()
+        w = oracle_weights(shape, seed, dtype=np.float32, device=dev)
+        kv = co.OracleKV.empty(shape, ctx + r, np.float32)
+        t_step, t_first = timed(shape, w, kv, 3)
+        return {
+            "value": r / t_step, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": (f"oracle verify step at full depth ({shape.n_layers} layers, fp32 numpy, r={r}, ctx={ctx}), median of 3 "
+                       f"= {t_step:.2f} s after one warm-up call ({t_first:.1f} s incl. generating the weights); the cache "
+                       f"holds zeros, not a prefilled context (timing does not depend on the values); {time.time() - t0:.0f} s in all"),
+        }
+    s4 = shape.with_layers(4)
+    w = oracle_weights(s4, seed, dtype=np.float32, device=dev)
+    kv = co.OracleKV.empty(s4, ctx + r, np.float32)
+    t4, _ = timed(s4, w, kv, 10)
+    t2, _ = timed(shape.with_layers(2), w, kv, 10)
+    per_layer = max(t4 - t2, 0.0) / 2
+    t_full = t2 + (shape.n_layers - 2) * per_layer
     return {
-        "value": r / t_full,
-        "unit": "tokens/s",
-        "cores": int(threads),
-        "kind": "oracle",
-        "sample": (f"oracle verify step (fp32 numpy, r={r}, ctx={ctx}), median of 10 at depth 2 ({t1:.3f} s) and "
-                   f"depth 4 ({t2:.3f} s) of {shape.n_layers}, same widths and vocabulary head; "
-                   f"full depth extrapolated linearly to {t_full:.2f} s; untimed oracle prefill {t_prefill:.1f} s"),
+        "value": r / t_full, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"oracle verify step (fp32 numpy, r={r}, ctx={ctx}), median of 10 at depth 2 ({t2:.3f} s) and "
+                   f"depth 4 ({t4:.3f} s) of {shape.n_layers}, same widths and vocabulary head; EXTRAPOLATED linearly "
+                   f"to full depth: {t_full:.2f} s (host memory too small for the fp32 weights)"),
     }
+
+
+class Rig:
+    """A target model of one shape with its weights, and the pieces the timed loops need."""
+
+    def __init__(self, shape, seed, max_ctx):
+        import torch
+
+        import paper_2508_04462_amd as card
+        from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+        self.card, self.torch = card, torch
+        self.shape, self.seed = shape, seed
+        self.tgt = card.Target(shape, max_ctx + 64, max_r=32)
+        load_synthetic_weights(self.tgt, shape, seed)
+        self.ctx = None
+        self.g0 = None
+
+    def set_context(self, ctx):
+        """Cache contents for a context of `ctx` tokens: prefilled from seeded uniform tokens through
+        the library up to PREFILL_MAX_CTX, noise pages beyond (perf-only points).  Returns the kind."""
+        import card_inputs as ci
+
+        torch, tgt = self.torch, self.tgt
+        self.ctx = ctx
+        if ctx <= PREFILL_MAX_CTX:
+            toks = ci.uniform_tokens(self.seed, "ctx_tokens", 0, ctx, self.shape.vocab).tolist()
+            self.g0 = tgt.prefill(toks)
+            return "prefilled"
+        g = torch.Generator(device=tgt.device)
+        g.manual_seed(self.seed)
+        for pool in (tgt.k_pages, tgt.v_pages):
+            v = pool.view(torch.bfloat16)
+            for i in range(0, v.numel(), 1 << 28):
+                v[i:i + (1 << 28)].normal_(0.0, 0.5, generator=g)
+        self.g0 = 1
+        return "noise"
+
+    def greedy(self, n):
+        """The target's own greedy continuation g0 .. g_n (plain decode steps, r = 1)."""
+        out, pos = [self.g0], self.ctx
+        for _ in range(n):
+            res = self.tgt.verify(pos, out[-1], [out[-1]])
+            out.append(res["correction_token"])
+            pos += 1
+        return out
+
+    def planted(self, r):
+        """Planted-prefix candidates for every j in 0..r, checked on the path that is timed."""
+        import card_inputs as ci
+
+        greedy = self.greedy(r)
+        cands = [ci.plant_candidates(greedy, j, r, self.shape.vocab, self.seed, stream=j) for j in range(r + 1)]
+        for j in range(r + 1):
+            res = self.tgt.verify(self.ctx, self.g0, cands[j])
+            if res["accepted_len"] != j or res["correction_token"] != greedy[j]:
+                raise RuntimeError(f"planted prefix {j} gave {res}")
+        return cands
+
+    def time_steps(self, r, cand_dev, steps, warmup, n_prof):
+        """(wall ms per step over `steps` calls, [kernel ms of n_prof further launches])."""
+        torch, card, tgt = self.torch, self.card, self.tgt
+        n = cand_dev.shape[0]
+
+        def step(i):
+            st = tgt.enqueue_verify(self.ctx, self.g0, r, cand=cand_dev[i % n])
+            if st != card.CARD_OK:
+                raise card.CardError(st, "card_verify")
+
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        # the whole step is ONE kernel: its launch duration comes from a HIP event pair recorded by
+        # the library around every launch, on the stream the kernel is launched on
+        card.card_profile_enable(n_prof)
+        for i in range(n_prof):
+            step(i)
+        torch.cuda.synchronize()
+        _, ms_each = card.card_profile_collect(n_prof)
+        return ms, ms_each
+
+    def close(self):
+        self.tgt = None
+        gc.collect()
+        self.torch.cuda.empty_cache()
+
+
+def sweep_point(rig, r, steps, kv_kind, planted=True):
+    torch, shape = rig.torch, rig.shape
+    import card_inputs as ci
+
+    cands = None
+    if planted and kv_kind == "prefilled":
+        try:
+            cands = rig.planted(r)
+            cand_note = f"planted prefix j cycling 0..{r}"
+        except RuntimeError as e:  # a near-tie between the r = 1 decode steps and the r-row step
+            cand_note = f"uniform candidates ({e})"
+    else:
+        cand_note = "uniform candidates"
+    if cands is None:
+        cands = [ci.uniform_tokens(rig.seed, "cand_tokens", j, r, shape.vocab).tolist() for j in range(4)]
+    cand_dev = torch.tensor(cands, dtype=torch.int32, device=rig.tgt.device)
+    ms, ms_each = rig.time_steps(r, cand_dev, steps, max(3, steps // 4), steps)
+    k_ms = sum(ms_each) / len(ms_each)
+    byts = step_bytes(shape, rig.ctx)
+    return {"shape": shape.name, "ctx": rig.ctx, "r": r, "kv": kv_kind, "candidates": cand_note, "steps": steps,
+            "ms_per_step": ms, "kernel_ms": k_ms, "verified_tokens_per_s": r / (ms * 1e-3),
+            "hbm_frac": byts / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": byts}
+
+
+def cache_loop(rig, r, p, n_tokens, K=50, width=10):
+    """Query / verify / correct against the shared candidate cache (host object of the library) with
+    a scripted draft: per position the best path holds the target's own greedy token with
+    probability p (independent draws, so the accepted length is truncated-geometric), K nodes per
+    level, depth r.  Every step waits for its result: the next query needs the verified tokens.
+    Returns accepted tokens/s over the loop (cache writes, query, step, correction all inside)."""
+    import numpy as np
+
+    card, tgt, shape = rig.card, rig.tgt, rig.shape
+    truth = rig.greedy(n_tokens + r + 1)
+    rng = np.random.default_rng(rig.seed)
+    cache = card.CandidateCache(K=K, max_depth=r)
+
+    def draft(e):
+        cache.write(0, [truth[e]], [-1], [1.0])
+        alive, prev = True, 1
+        for i in range(1, r):
+            right = truth[e + i]
+            good = alive and rng.random() < p
+            n = K if i > 1 else min(K, width)
+            toks = [(right + 1 + k) % shape.vocab for k in range(n)]
+            if good:
+                toks[0] = right
+            elif alive and rng.random() < 0.5:
+                toks[1] = right  # the right token sits on a lower-scored sibling
+            parents = [0] * min(n, width) + [int(rng.integers(0, prev)) for _ in range(n - min(n, width))]
+            scores = [0.9 ** i] + [0.5 ** i * 0.98 ** k for k in range(1, n)]
+            cache.write(i, toks, parents, scores)
+            alive, prev = good, n
+
+    pos, pending, emitted, steps, hits, left_at = rig.ctx, truth[0], 0, 0, 0, None
+    rig.torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while emitted < n_tokens:
+        draft(emitted)
+        hit, path, _ = cache.query(pending, r)
+        cand = path if hit else [pending]
+        hits += int(hit)
+        res = tgt.verify(pos, pending, cand)
+        a = res["accepted_len"]
+        if a < 1 or res["correction_token"] != truth[emitted + a]:
+            # a near-tie decided differently by the r = 1 steps that wrote `truth`: stop here
+            left_at = emitted
+            break
+        cache.correct(cand[:a] + [res["correction_token"]])
+        pos += res["kv_count"]
+        pending = res["correction_token"]
+        emitted += a
+        steps += 1
+    dt = time.perf_counter() - t0
+    if steps == 0:
+        return {"shape": shape.name, "ctx": rig.ctx, "r": r, "kind": "cache_loop", "planted_acceptance": p,
+                "error": "the first step already left the greedy text (near-tie)"}
+    return {"shape": shape.name, "ctx": rig.ctx, "r": r, "kind": "cache_loop", "planted_acceptance": p, "K": K,
+            "left_greedy_text_at": left_at, "steps": steps, "hit_rate": hits / steps, "mean_accepted_len": emitted / steps,
+            "ms_per_step": dt * 1e3 / steps, "accepted_tokens_per_s": emitted / dt,
+            "plain_decode_tokens_per_s": None}
+
+
+def run_sweep(args, rig8b):
+    """Every synthetic configuration besides the headline one.  rig8b: the headline model, reused."""
+    import card_inputs as ci
+
+    out = []
+    quick = args.sweep == "quick"
+    # context sweep on the 8B shape, r = 8
+    for ctx in ([512] if quick else [512, 2048, 8192, 32768]):
+        if ctx + 64 > rig8b.tgt.cfg.max_ctx:
+            continue
+        kind = rig8b.set_context(ctx)
+        out.append(sweep_point(rig8b, 8, 10 if quick else 20, kind))
+    if quick:
+        rig8b.set_context(256)
+        e = cache_loop(rig8b, 8, 0.6, 16)
+        out.append(e)
+        return out
+    rig8b.close()
+    # Qwen-7B shape, context 4096: r sweep and the shared-cache loop
+    shape = ci.SHAPES["qwen7b"]
+    rig = Rig(shape, args.seed, shape.ctx + 160)
+    kind = rig.set_context(shape.ctx)
+    for r in (1, 2, 4, 8, 16, 32):
+        out.append(sweep_point(rig, r, 20, kind))
+    rig.set_context(2048)  # the loop needs the target's real greedy text: a prefilled context
+    t0 = time.perf_counter()
+    n_dec = 24
+    rig.greedy(n_dec)
+    decode_tps = n_dec / (time.perf_counter() - t0)
+    for p in (0.3, 0.6, 0.9):
+        e = cache_loop(rig, 8, p, 96)
+        e["plain_decode_tokens_per_s"] = decode_tps
+        out.append(e)
+    rig.close()
+    # 70B shape, context 2048
+    shape = ci.SHAPES["llama70b"]
+    rig = Rig(shape, args.seed, shape.ctx)
+    kind = rig.set_context(shape.ctx)
+    for r in (4, 8, 16):
+        out.append(sweep_point(rig, r, 8, kind))
+    rig.close()
+    return out
 
 
 def main():
@@ -109,7 +344,6 @@ def main():
 
     import card_inputs as ci
     import paper_2508_04462_amd as card
-    from paper_2508_04462_amd.synthetic import load_synthetic_weights
 
     shape = ci.SHAPES[args.shape]
     ctx = shape.ctx if args.ctx is None else args.ctx
@@ -117,29 +351,15 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    tgt = card.Target(shape, ctx + 64, max_r=32)
-    load_synthetic_weights(tgt, shape, args.seed)
-    ctx_tokens = ci.uniform_tokens(args.seed, "ctx_tokens", 0, ctx, shape.vocab).tolist()
-    g0 = tgt.prefill(ctx_tokens)
-    # the target's own greedy continuation (plain decode steps, r = 1) to plant prefixes from
-    greedy, n = [g0], ctx
-    for _ in range(r):
-        res = tgt.verify(n, greedy[-1], [greedy[-1]])
-        greedy.append(res["correction_token"])
-        n += 1
-    cands = [ci.plant_candidates(greedy, j, r, shape.vocab, args.seed, stream=j) for j in range(r + 1)]
+    sweep_ctx = 0 if args.sweep == "none" or args.shape != "llama8b" else (512 if args.sweep == "quick" else 32768)
+    rig = Rig(shape, args.seed, max(ctx, sweep_ctx))
+    rig.set_context(ctx)
+    try:
+        cands = rig.planted(r)  # planted-prefix invariant on the path being timed
+    except RuntimeError as e:
+        print(f"bench.py: {e}", file=sys.stderr)
+        sys.exit(1)
     cand_dev = torch.tensor(cands, dtype=torch.int32, device=dev)
-    # planted-prefix invariant on the path being timed
-    for j in range(r + 1):
-        res = tgt.verify(ctx, g0, cands[j])
-        if res["accepted_len"] != j or res["correction_token"] != greedy[j]:
-            print(f"bench.py: planted prefix {j} gave {res}", file=sys.stderr)
-            sys.exit(1)
-
-    def step(i):
-        st = tgt.enqueue_verify(ctx, g0, r, cand=cand_dev[i % (r + 1)])
-        if st != card.CARD_OK:
-            raise card.CardError(st, "card_verify")
 
     if args.pmc_probe:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -147,38 +367,22 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         for i in range(5):
-            step(i)
+            st = rig.tgt.enqueue_verify(ctx, rig.g0, r, cand=cand_dev[i % (r + 1)])
+            assert st == card.CARD_OK
         torch.cuda.synchronize()
         print(json.dumps({"pmc_probe": True, "copy_bytes": 1 << 30, "verify_steps": 5}))
         return
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-
-    # roofline of the dominant kernel.  The whole step is ONE kernel (k_verify), so its launch
-    # duration is measured with a HIP event pair around every launch, recorded by the library on
-    # the stream the kernel is launched on, over a second pass of the same loop.
-    n_prof = min(args.steps, 100)
-    card.card_profile_enable(n_prof)
-    for i in range(n_prof):
-        step(i)
-    torch.cuda.synchronize()
-    st, ms_each = card.card_profile_collect(n_prof)
+    ms_per_step, ms_each = rig.time_steps(r, cand_dev, args.steps, args.warmup, min(args.steps, 100))
     kbytes = step_bytes(shape, ctx)
     k_ms = sum(ms_each) / max(len(ms_each), 1)
     achieved = kbytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
-    traffic = None
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get(f"{args.shape}:ctx{ctx}:r{r}")
+            traffic_src = "stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/, not measured in this run"
         except Exception:
             traffic = None
 
@@ -205,12 +409,18 @@ def main():
                    "global_batch": 1, "seq_len": ctx, "r": r, "parallelism": "single GPU"},
         "roofline": {"bound": "hbm", "kernel": "k_verify (whole step, one persistent kernel)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
                      "bytes_per_launch": kbytes, "avg_launch_us": k_ms * 1e3, "launches_timed": len(ms_each)},
         "paper_context": PAPER_CONTEXT,
     }
+    if args.sweep != "none" and args.shape == "llama8b":
+        t0 = time.perf_counter()
+        out["sweep"] = run_sweep(args, rig)
+        out["sweep_seconds"] = time.perf_counter() - t0
+    rig.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, args.seed, ctx, r, cands[r])
+    card.card_profile_disable()
     print(json.dumps(out))
 
 

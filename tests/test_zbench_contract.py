@@ -23,11 +23,9 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 @pytest.mark.gpu
 def test_short_run_prints_one_json_line_with_the_contract_fields(monkeypatch, capsys):
-    # in this process: run as a child of a test process that has already used the GPU, bench.py's
-    # first cooperative launch came back with a device error
     import runpy
 
-    monkeypatch.setattr(sys, "argv", ["bench.py", "--steps", "6", "--warmup", "2", "--no-cpu-baseline"])
+    monkeypatch.setattr(sys, "argv", ["bench.py", "--steps", "6", "--warmup", "2", "--no-cpu-baseline", "--sweep", "quick"])
     monkeypatch.chdir(ROOT)
     runpy.run_path(os.path.join(ROOT, "bench.py"), run_name="__main__")
     lines = [ln for ln in capsys.readouterr().out.splitlines() if ln.strip()]
@@ -44,3 +42,10 @@ def test_short_run_prints_one_json_line_with_the_contract_fields(monkeypatch, ca
     assert 0.2 < rf["frac"] < 1.0
     assert abs(rf["achieved"] - d["algorithmic_bytes_per_step"] / (rf["avg_launch_us"] * 1e-6) / 1e9) <= 1e-6 * rf["achieved"]
     assert rf["traffic"] is None or rf["traffic"] >= 0.9 * d["algorithmic_bytes_per_step"]
+    # the other synthetic configurations ride in the same line
+    sw = d["sweep"]
+    pts = [e for e in sw if e.get("kind") != "cache_loop"]
+    assert pts and all(e["ms_per_step"] > 0 and 0.1 < e["hbm_frac"] < 1.0 and e["verified_tokens_per_s"] > 0 for e in pts)
+    loops = [e for e in sw if e.get("kind") == "cache_loop"]
+    assert loops and all("error" in e or (e["accepted_tokens_per_s"] > 0 and 1.0 <= e["mean_accepted_len"] <= e["r"])
+                         for e in loops)
