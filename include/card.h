@@ -174,6 +174,34 @@ int card_verify(const card_model_cfg* cfg, const void* packed_weights_dev, const
                 int32_t ctx_len, const int32_t* cand_tokens_dev, int32_t r, void* workspace_dev,
                 void* stream, card_verify_result* out_dev, int32_t* row_argmax_dev);
 
+/* Verification at a sampling temperature (Experimental Setup: temperature 1.0 columns of the main
+ * results; CARD Design: the target keeps the sampling mechanism of speculative decoding, so the
+ * output is distributed as the target's own sampling).  The paper gives no formula; the reading
+ * taken here: the path the cache returns is a deterministic proposal (a point mass on each
+ * candidate), for which speculative sampling accepts candidate c with probability p(c) and on a
+ * rejection emits a draw from p restricted to the other tokens.  Both come from ONE draw x ~ p per
+ * position: accept iff x == c, else emit x.  The draw is arg-max_v (logit_v / T + G(seed, pos, v))
+ * with G standard Gumbel noise from a counter-based generator keyed by the seed, the absolute
+ * position of the token being drawn and the token id v:
+ *     mix(x): x ^= x>>16; x *= 0x7feb352d; x ^= x>>15; x *= 0x846ca68b; x ^= x>>16   (32-bit)
+ *     key = mix(mix(mix(seed_lo ^ 0x243f6a88) ^ seed_hi) ^ pos);  h = mix(key + v * 0x9e3779b9)
+ *     u = ((h >> 8) + 0.5) / 2^24;  G = -ln(-ln(u))
+ * so a position's token does not depend on which call computes its row: a chain of these steps
+ * emits exactly the text that token-by-token sampling with the same seed emits, whatever the
+ * candidates were.  temperature == 0 is card_verify.  pred[0] = kv->pending_token as before (the
+ * previous call's correction token, itself such a draw).  row_token_dev receives the r draws;
+ * logits_dev (optional, may be NULL; test use) the fp32 logits [r][vocab] before temperature and
+ * noise. */
+typedef struct card_sampling {
+    float temperature; /* >= 0 */
+    uint64_t seed;
+} card_sampling;
+
+int card_verify_sampled(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
+                        int32_t ctx_len, const int32_t* cand_tokens_dev, int32_t r,
+                        const card_sampling* sampling, void* workspace_dev, void* stream,
+                        card_verify_result* out_dev, int32_t* row_token_dev, float* logits_dev);
+
 /* card_verify for callers that cannot allocate device memory or hand a workspace over: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same step, same
  * results; the workspace is a 32 MiB array that lives in the library's code object (each GPU the

@@ -28,7 +28,8 @@ used by pins that compare with closed forms).
 Pins (tests/test_oracle_*.py): row-batched verify == token-by-token decode ==
 cache-free full recompute (a separate code path below); planted-prefix
 invariant; rotary, norm, softmax and GQA identities; blocks against torch's
-CPU library routines.  Absolute logit values have no printed example in the
+CPU library routines; sampling: draw frequencies against the softmax (chi-square),
+acceptance rate against p(c), chained steps against token-by-token sampling.  Absolute logit values have no printed example in the
 paper to compare with: "parity unpinned" beyond those pins.
 """
 from __future__ import annotations
@@ -187,6 +188,43 @@ def top2_gap(row: np.ndarray) -> float:
     return float(part[-1] - part[-2])
 
 
+# --------------------------------------------------------------------------- sampling
+
+
+def _mix32(x: np.ndarray) -> np.ndarray:
+    """32-bit xorshift-multiply finaliser ("lowbias32", C. Wellons, public domain) on uint64 lanes."""
+    m = np.uint64(0xFFFFFFFF)
+    x = x & m
+    x = x ^ (x >> np.uint64(16))
+    x = (x * np.uint64(0x7FEB352D)) & m
+    x = x ^ (x >> np.uint64(15))
+    x = (x * np.uint64(0x846CA68B)) & m
+    x = x ^ (x >> np.uint64(16))
+    return x
+
+
+def gumbel_noise(seed: int, pos: int, vocab: int) -> np.ndarray:
+    """Standard Gumbel noise G[v], v in [0, vocab), for the token drawn at absolute position pos:
+    a counter-based generator (the draw for a position must not depend on which step computes
+    it).  key = mix(mix(mix(seed_lo ^ 0x243f6a88) ^ seed_hi) ^ pos); h = mix(key + v * 0x9e3779b9);
+    u = ((h >> 8) + 1/2) / 2^24 in (0, 1); G = -ln(-ln u)."""
+    lo, hi = np.uint64(seed & 0xFFFFFFFF), np.uint64((seed >> 32) & 0xFFFFFFFF)
+    key = _mix32(_mix32(_mix32(np.array([lo ^ np.uint64(0x243F6A88)], dtype=np.uint64)) ^ hi) ^ np.uint64(pos & 0xFFFFFFFF))
+    v = np.arange(vocab, dtype=np.uint64)
+    h = _mix32((key + v * np.uint64(0x9E3779B9)) & np.uint64(0xFFFFFFFF))
+    u = ((h >> np.uint64(8)).astype(np.float64) + 0.5) / 16777216.0
+    return -np.log(-np.log(u))
+
+
+def perturbed(row: np.ndarray, pos: int, temperature: float, seed: int) -> np.ndarray:
+    """logits / T + G(seed, pos, .): its arg-max is a draw from softmax(logits / T) (the maximum of
+    independently Gumbel-shifted scores falls on index v with probability softmax(score)[v]).
+    Temperature 0 returns the logits themselves (greedy)."""
+    if temperature <= 0.0:
+        return row
+    return row.astype(np.float64) / temperature + gumbel_noise(seed, pos, row.shape[0])
+
+
 # --------------------------------------------------------------------------- acceptance
 
 
@@ -218,12 +256,23 @@ def greedy_accept(pending: int, row_argmax: Sequence[int], cand: Sequence[int]) 
 
 
 def verify(
-    cfg, w, kv, ctx_len: int, pending: int, cand: Sequence[int], dtype=np.float64, keep_logits=False
+    cfg, w, kv, ctx_len: int, pending: int, cand: Sequence[int], dtype=np.float64, keep_logits=False,
+    temperature: float = 0.0, seed: int = 0,
 ) -> VerifyResult:
-    """One verification step: forward the r candidates at positions ctx_len.., then accept."""
+    """One verification step: forward the r candidates at positions ctx_len.., then accept.
+
+    Temperature 0 (the paper's main setting): the target's token after row i is the arg-max of
+    row i.  Temperature > 0 (the T = 1 columns of the main results; the paper states only that the
+    sampling mechanism of speculative decoding is kept): the cached path is a deterministic
+    proposal, for which speculative sampling accepts candidate c with probability p(c) and
+    otherwise emits a draw from p restricted to the other tokens; one draw x ~ p per position
+    gives both (accept iff x == c, else emit x).  Row i's draw is for position ctx_len + i + 1 and
+    uses that position's noise, so the same prefix rule applies with draws in place of arg-maxes.
+    row_argmax / row_gap then hold the draws and the top-1/top-2 gaps of the perturbed rows."""
     logits = forward_rows(cfg, w, kv, cand, ctx_len, dtype)
-    am = [argmax_lowest(row) for row in logits]
-    gaps = [top2_gap(row) for row in logits]
+    scored = [perturbed(row, ctx_len + i + 1, temperature, seed) for i, row in enumerate(logits)]
+    am = [argmax_lowest(row) for row in scored]
+    gaps = [top2_gap(row) for row in scored]
     j, corr = greedy_accept(pending, am, cand)
     return VerifyResult(j, corr, ctx_len, j, am, gaps, logits if keep_logits else None)
 
@@ -274,27 +323,32 @@ def full_recompute(cfg, w: OracleWeights, tokens: Sequence[int], dtype=np.float6
 
 
 def greedy_decode_bruteforce(
-    cfg, w, ctx_tokens: Sequence[int], n_new: int, dtype=np.float64, store: str = "bf16"
+    cfg, w, ctx_tokens: Sequence[int], n_new: int, dtype=np.float64, store: str = "bf16",
+    temperature: float = 0.0, seed: int = 0,
 ) -> List[int]:
-    """Plain autoregressive greedy decoding, one token at a time, recomputing the whole
-    sequence each time.  Returns [g0, g1, ..., g_{n_new-1}]."""
+    """Plain autoregressive decoding, one token at a time, recomputing the whole sequence each
+    time: greedy at temperature 0, else sampling (the token at position p is the arg-max of the
+    last row's logits / T + G(seed, p, .)).  Returns [g0, g1, ..., g_{n_new-1}]."""
     seq = [int(t) for t in ctx_tokens]
     out = []
     for _ in range(n_new):
         logits = full_recompute(cfg, w, seq, dtype, store)
-        nxt = argmax_lowest(logits[-1])
+        nxt = argmax_lowest(perturbed(logits[-1], len(seq), temperature, seed))
         out.append(nxt)
         seq.append(nxt)
     return out
 
 
-def greedy_decode_cached(cfg, w, kv, ctx_len: int, pending: int, n_new: int, dtype=np.float64):
-    """Autoregressive greedy decoding with the KV cache: feeds the pending token, then each
-    prediction in turn.  Returns ([pending, g1, ..., g_{n_new}], gaps of g1..)."""
+def greedy_decode_cached(cfg, w, kv, ctx_len: int, pending: int, n_new: int, dtype=np.float64,
+                         temperature: float = 0.0, seed: int = 0):
+    """Autoregressive decoding with the KV cache (greedy, or sampling at a temperature > 0): feeds
+    the pending token, then each prediction in turn.  Returns ([pending, g1, ..., g_{n_new}], gaps
+    of g1..; at a temperature the gaps of the perturbed rows)."""
     toks = [int(pending)]
     gaps = []
     for i in range(n_new):
         logits = forward_rows(cfg, w, kv, [toks[-1]], ctx_len + i, dtype)
-        toks.append(argmax_lowest(logits[0]))
-        gaps.append(top2_gap(logits[0]))
+        row = perturbed(logits[0], ctx_len + i + 1, temperature, seed)
+        toks.append(argmax_lowest(row))
+        gaps.append(top2_gap(row))
     return toks, gaps

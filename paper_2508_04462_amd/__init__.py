@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     CardModelCfg,
     CardKV,
     CardVerifyResult,
+    CardSampling,
     lib,
     lib_path,
     card_strerror,
@@ -30,6 +31,7 @@ from .binding import (  # noqa: F401
     card_verify,
     card_verify_debug_logits,
     card_verify_static,
+    card_verify_sampled,
     card_static_scratch_bytes,
     card_static_scratch_reset,
     card_kv_gather,

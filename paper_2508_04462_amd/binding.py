@@ -38,6 +38,10 @@ class CardKV(C.Structure):
     ]
 
 
+class CardSampling(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("seed", C.c_uint64)]
+
+
 class CardVerifyResult(C.Structure):
     _fields_ = [
         ("accepted_len", C.c_int32), ("correction_token", C.c_int32),
@@ -77,6 +81,8 @@ def _declare(lib: C.CDLL) -> C.CDLL:
     lib.card_workspace_init.argtypes = [_cfgp, _P, _P]
     lib.card_verify.restype = C.c_int
     lib.card_verify.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P]
+    lib.card_verify_sampled.restype = C.c_int
+    lib.card_verify_sampled.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, C.POINTER(CardSampling), _P, _P, _P, _P, _P]
     lib.card_verify_static.restype = C.c_int
     lib.card_verify_static.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P]
     lib.card_static_scratch_bytes.restype = C.c_size_t
@@ -168,6 +174,13 @@ def card_verify(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: int, wor
                 out_dev, row_argmax_dev=None) -> int:
     return lib.card_verify(C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, _ptr(cand_dev), r,
                            _ptr(workspace_dev), _ptr(stream), _ptr(out_dev), _ptr(row_argmax_dev))
+
+
+def card_verify_sampled(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: int, sampling: CardSampling,
+                        workspace_dev, stream, out_dev, row_token_dev=None, logits_dev=None) -> int:
+    return lib.card_verify_sampled(C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, _ptr(cand_dev), r,
+                                   C.byref(sampling), _ptr(workspace_dev), _ptr(stream), _ptr(out_dev),
+                                   _ptr(row_token_dev), _ptr(logits_dev))
 
 
 def card_verify_static(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: int, stream, out_dev,

@@ -130,7 +130,7 @@ std::mutex g_static_mu;
 // One persistent kernel runs the whole step (card_verify.hip).
 int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv, int32_t ctx_len,
                 const int32_t* cand, int32_t r, void* workspace, void* stream, card_verify_result* out,
-                int32_t* row_argmax, float* logits) {
+                int32_t* row_argmax, float* logits, const card_sampling* sampling = nullptr) {
     if (!cfg || !packed || !kv || !cand || !workspace || !out) return CARD_EINVAL;
     const Layout L = make_layout(cfg);
     if (!L.ok) return CARD_EINVAL;
@@ -210,6 +210,11 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.flags = reinterpret_cast<uint32_t*>(ws + L.m_flags_off);
     a.cand = cand;
     a.pending = kv->pending_token;
+    if (sampling && sampling->temperature > 0.f) {
+        a.inv_temp = 1.0f / sampling->temperature;
+        a.seed_lo = uint32_t(sampling->seed & 0xffffffffull);
+        a.seed_hi = uint32_t(sampling->seed >> 32);
+    }
     a.out = out;
     a.row_argmax = row_argmax;
     a.logits = logits;
@@ -325,6 +330,14 @@ int card_verify(const card_model_cfg* cfg, const void* packed_weights_dev, const
                 card_verify_result* out_dev, int32_t* row_argmax_dev) {
     return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, workspace_dev, stream, out_dev,
                        row_argmax_dev, nullptr);
+}
+
+int card_verify_sampled(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv, int32_t ctx_len,
+                        const int32_t* cand_tokens_dev, int32_t r, const card_sampling* sampling, void* workspace_dev,
+                        void* stream, card_verify_result* out_dev, int32_t* row_token_dev, float* logits_dev) {
+    if (!sampling || !(sampling->temperature >= 0.f)) return CARD_EINVAL;
+    return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, workspace_dev, stream, out_dev,
+                       row_token_dev, logits_dev, sampling);
 }
 
 int card_verify_static(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv, int32_t ctx_len,

@@ -77,6 +77,8 @@ struct MegaArgs {
     uint32_t* acount;  // [Hkv * row_tiles] arrival counters of the attention cuts; zero between uses
     const int32_t* cand;
     int32_t pending;
+    float inv_temp;          // 0: greedy (arg-max of the logits); > 0: sample, logits / temperature + Gumbel noise
+    uint32_t seed_lo, seed_hi;
     card_verify_result* out;
     int32_t* row_argmax;
     float* logits;
@@ -386,6 +388,31 @@ __device__ __forceinline__ void fifo_wait(MegaSmem& sm, FifoC& f, int w, uint32_
     }
     f.waited += uint32_t(wall_clock64() - w0);
     asm volatile("" ::: "memory");
+}
+
+// ---- sampling ------------------------------------------------------------------------------------
+// Temperature > 0: the target's token for a position is a draw from softmax(logits / T), taken as
+// arg-max of logits / T + G with G standard Gumbel noise (the maximum of Gumbel-perturbed logits is
+// distributed as the softmax).  The noise is a pure function of (seed, position, token id): a
+// counter-based generator, so a position gets the same draw whether its row is computed in a
+// verification step or in a plain decode step, and verification reproduces token-by-token
+// sampling exactly.  32-bit mixer: two-multiply xorshift finaliser ("lowbias32", C. Wellons,
+// public domain); 24 bits of it give u = (k + 1/2) / 2^24 in (0, 1), exact in fp32.
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ uint32_t gumbel_row_key(uint32_t seed_lo, uint32_t seed_hi, uint32_t pos) {
+    return mix32(mix32(mix32(seed_lo ^ 0x243f6a88u) ^ seed_hi) ^ pos);
+}
+__device__ __forceinline__ float gumbel_noise(uint32_t row_key, uint32_t token) {
+    const uint32_t h = mix32(row_key + token * 0x9e3779b9u);
+    const float u = (float(h >> 8) + 0.5f) * (1.0f / 16777216.0f);
+    return -logf(-logf(u));
 }
 
 enum MegaEpi { ME_QKV = 0, ME_RESID = 1, ME_SWIGLU = 2, ME_LM = 3 };
@@ -709,13 +736,17 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                 unsigned long long best = 0ull;
                 if (m < r) {
                     const float sc = sm.row_scale[m];
+                    // row m predicts the token at position ctx_len + m + 1
+                    const uint32_t rkey = gumbel_row_key(a.seed_lo, a.seed_hi, uint32_t(a.ctx_len + m + 1));
 #pragma unroll
                     for (int q = 0; q < ROWS_PER; ++q) {
                         const int nl = part * ROWS_PER + q, i = nl >> 4;
                         const int n = (tile0 + i * a.nwg) * 16 + (nl & 15);
                         if (i < nvalid_s && n < a.V) {
+                            float val = sm.tile[nl * COLS + m] * sc;
+                            if (a.inv_temp > 0.f) val = val * a.inv_temp + gumbel_noise(rkey, uint32_t(n));
                             const unsigned long long key =
-                                (static_cast<unsigned long long>(float_key(sm.tile[nl * COLS + m] * sc)) << 32) |
+                                (static_cast<unsigned long long>(float_key(val)) << 32) |
                                 (0xffffffffu - uint32_t(n));
                             best = key > best ? key : best;
                         }

@@ -67,25 +67,30 @@ class Target:
 
     # -- one verification step
     def enqueue_verify(self, ctx_len: int, pending: int, r: int, logits: Optional[torch.Tensor] = None,
-                       cand: Optional[torch.Tensor] = None) -> int:
+                       cand: Optional[torch.Tensor] = None, sampling: Optional[B.CardSampling] = None) -> int:
         """Enqueue on the current stream; candidates come from `cand` (device int32) or from
         self.cand[:r].  No synchronisation."""
         kv = self.kv(pending)
         cand = self.cand if cand is None else cand
+        if sampling is not None:
+            return B.card_verify_sampled(self.cfg, self.packed, kv, ctx_len, cand, r, sampling, self.workspace,
+                                         self._stream(), self.out, self.row_argmax, logits)
         if logits is None:
             return B.card_verify(self.cfg, self.packed, kv, ctx_len, cand, r, self.workspace,
                                  self._stream(), self.out, self.row_argmax)
         return B.card_verify_debug_logits(self.cfg, self.packed, kv, ctx_len, cand, r, self.workspace,
                                           self._stream(), self.out, self.row_argmax, logits)
 
-    def verify(self, ctx_len: int, pending: int, cand: Sequence[int], want_logits: bool = False) -> Dict:
+    def verify(self, ctx_len: int, pending: int, cand: Sequence[int], want_logits: bool = False,
+               temperature: float = 0.0, seed: int = 0) -> Dict:
         r = len(cand)
         if 0 < r <= 32:
             self.cand[:r] = torch.tensor([int(c) for c in cand], dtype=torch.int32, device=self.device)
         logits = None
         if want_logits:
             logits = torch.empty((max(r, 1), self.cfg.vocab), dtype=torch.float32, device=self.device)
-        _check(self.enqueue_verify(ctx_len, pending, r, logits), "card_verify")
+        sampling = B.CardSampling(float(temperature), int(seed)) if temperature > 0 else None
+        _check(self.enqueue_verify(ctx_len, pending, r, logits, sampling=sampling), "card_verify")
         torch.cuda.current_stream(self.device).synchronize()
         o = self.out.tolist()
         res = {"accepted_len": o[0], "correction_token": o[1], "kv_first_slot": o[2], "kv_count": o[3],

@@ -329,3 +329,89 @@ def test_greedy_decode_cached_equals_bruteforce_and_its_gaps_are_the_recomputed_
     ref = co.full_recompute(cfg, w, ctx + toks, store=store)[-1]
     np.testing.assert_allclose(nxt, ref, rtol=1e-10, atol=1e-12)
 
+
+
+# ----------------------------------------------------------------------------- sampling (temperature > 0)
+
+
+def test_mixer_and_uniforms_of_the_noise_generator():
+    # the mixer against the generators' own copy of the published function, and its fixed point
+    x = np.array([0, 1, 2, 0xDEADBEEF, 0xFFFFFFFF, 123456789], dtype=np.uint64)
+    assert co._mix32(x).tolist() == [ci.generate._mix32_int(int(v)) for v in x]
+    assert int(co._mix32(np.array([0], dtype=np.uint64))[0]) == 0
+    g = co.gumbel_noise(7, 1000, 4096)
+    u = np.exp(-np.exp(-g))
+    k = u * 2 ** 24 - 0.5  # u = (k + 1/2) / 2^24 with integer k: strictly inside (0, 1)
+    assert np.abs(k - np.round(k)).max() < 1e-6 and k.min() >= 0 and k.max() <= 2 ** 24 - 1
+    # another position, another seed half, another token: another draw
+    assert not np.array_equal(g, co.gumbel_noise(7, 1001, 4096))
+    assert not np.array_equal(g, co.gumbel_noise(7 + (1 << 32), 1000, 4096))
+    assert len(np.unique(g)) > 4000
+
+
+def test_noise_is_standard_gumbel():
+    g = np.concatenate([co.gumbel_noise(3, p, 2048) for p in range(200)])
+    assert abs(g.mean() - 0.5772156649) < 0.01  # Euler-Mascheroni
+    assert abs(g.var() - math.pi ** 2 / 6) < 0.03
+    # CDF exp(-exp(-x)) at a few points
+    for x in (-1.0, 0.0, 1.0, 3.0):
+        assert abs((g <= x).mean() - math.exp(-math.exp(-x))) < 0.005
+
+
+def test_draws_follow_the_softmax_and_acceptance_rate_is_p_of_the_candidate():
+    """Chi-square of the draw frequencies against softmax(logits / T), and the probability that the
+    draw equals a fixed candidate (= the acceptance probability of a point-mass proposal)."""
+    rng = _rng(11)
+    logits = rng.normal(size=12) * 1.5
+    for temp in (1.0, 0.7):
+        p = co.softmax(logits / temp)
+        n = 40000
+        draws = np.array([co.argmax_lowest(co.perturbed(logits, pos, temp, 99)) for pos in range(n)])
+        counts = np.bincount(draws, minlength=12)
+        chi2 = ((counts - n * p) ** 2 / (n * p)).sum()
+        assert chi2 < 40.0  # 11 degrees of freedom: 40 is beyond the 99.99 % point
+        c = int(np.argsort(p)[-2])
+        assert abs((draws == c).mean() - p[c]) < 4 * math.sqrt(p[c] * (1 - p[c]) / n)
+    # temperature -> 0 is the arg-max; temperature 0 leaves the row untouched
+    assert co.argmax_lowest(co.perturbed(logits, 5, 1e-4, 99)) == co.argmax_lowest(logits)
+    assert co.perturbed(logits, 5, 0.0, 99) is logits
+
+
+@pytest.mark.parametrize("seed", [2, 5])
+def test_chained_sampled_verify_reproduces_token_by_token_sampling(seed):
+    """Lossless at a temperature: whatever the candidates, chained verification steps emit exactly
+    the text that plain autoregressive sampling with the same seed emits (cache-free recompute per
+    token), and a planted prefix of that text is accepted to its full length."""
+    cfg = ODD
+    w = oracle_weights(cfg, seed, gain_jitter=0.2)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, cfg.ctx, cfg.vocab).tolist()
+    temp, rs = 1.0, 1000 + seed
+    want = co.greedy_decode_bruteforce(cfg, w, ctx, 12, temperature=temp, seed=rs)
+    assert want != co.greedy_decode_bruteforce(cfg, w, ctx, 12)  # it is not the greedy text
+    kv = co.OracleKV.empty(cfg, 64)
+    last = co.forward_rows(cfg, w, kv, ctx, 0)[-1]
+    pending = co.argmax_lowest(co.perturbed(last, cfg.ctx, temp, rs))
+    assert pending == want[0]
+    # planted prefixes of the sampled text
+    for j in range(cfg.r + 1):
+        cand = ci.plant_candidates(want, j, cfg.r, cfg.vocab, seed, stream=j)
+        res = co.verify(cfg, w, kv, cfg.ctx, pending, cand, temperature=temp, seed=rs)
+        assert (res.accepted_len, res.correction_token) == (j, want[j])
+    n, emitted, step = cfg.ctx, [pending], 0
+    while len(emitted) < 12:
+        guess = want[len(emitted): len(emitted) + 3]
+        cand = [pending] + [g if (step + i) % 3 else (g + 1) % cfg.vocab for i, g in enumerate(guess)]
+        res = co.verify(cfg, w, kv, n, pending, cand, temperature=temp, seed=rs)
+        emitted += cand[1: res.accepted_len] + [res.correction_token]
+        n += res.kv_count
+        pending = res.correction_token
+        step += 1
+    assert emitted[:12] == want
+    toks, _ = co.greedy_decode_cached(cfg, w, co_kv_prefilled(cfg, w, ctx), cfg.ctx, want[0], 6, temperature=temp, seed=rs)
+    assert toks == want[:7]
+
+
+def co_kv_prefilled(cfg, w, ctx):
+    kv = co.OracleKV.empty(cfg, 64)
+    co.prefill(cfg, w, kv, ctx)
+    return kv
