@@ -276,7 +276,7 @@ def cache_loop(rig, r, p, n_tokens, K=50, width=10):
             # a near-tie decided differently by the r = 1 steps that wrote `truth`: stop here
             left_at = emitted
             break
-        cache.correct(cand[:a] + [res["correction_token"]])
+        cache.correct(cand[:a])
         pos += res["kv_count"]
         pending = res["correction_token"]
         emitted += a

@@ -303,6 +303,42 @@ int32_t card_cache_depth(const card_cache* c);
 int card_cache_read_level(const card_cache* c, int32_t level, int32_t* tokens, int32_t* parent_idx,
                           float* path_score);
 
+/* ------------------------------------------------------------------------------------------
+ * One target step of the query-and-correct loop in two calls (overview figure: query the cache
+ * with the token just verified, verify the returned path, correct the cache with what was
+ * verified; Comparing with Tree-Verified Methods: the number of verified tokens varies from step
+ * to step with what the cache holds).
+ * card_step_begin: looks kv->pending_token (>= 0: the token verified last) up in the cache; on a
+ * hit the candidates are the returned path, 1..max_len tokens starting with that token; on a miss
+ * the step falls back to a plain decode step, r = 1, on the token itself.  The candidates are
+ * written to cand_staging (int32[max_len], host memory the device can read: pinned, allocated
+ * with hipHostMalloc) and the step is enqueued on `stream` like card_verify; `out` must be
+ * readable by the host after the stream has finished (pinned host memory, or copy it back).
+ * step_host (host) records the candidates for card_step_end.
+ * card_step_end, after the stream has finished: writes the tokens the step emitted (the accepted
+ * path tokens behind the query key, then the target's own token: out->accepted_len of them) to
+ * emitted_host (int32[max_len]) and re-roots the cache (card_cache_correct with the accepted
+ * candidates: level 0 then holds the children of the last accepted node, among which the next
+ * step looks the target's own token up).  flags = CARD_STEP_NO_CORRECT skips the
+ * correction: the "query without correct" variant of the ablation study, in which the cache is
+ * queried but never re-rooted by the target.  Returns CARD_EDEVICE if out reports a failed step.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct card_step {
+    int32_t r;          /* candidates forwarded by this step                     */
+    int32_t hit;        /* 1: the cache had a path for the token, 0: plain decode */
+    float path_score;   /* score of the returned path (0 on a miss)              */
+    int32_t cand[32];
+} card_step;
+
+enum { CARD_STEP_NO_CORRECT = 1 };
+
+int card_step_begin(card_cache* cache, const card_model_cfg* cfg, const void* packed_weights_dev,
+                    const card_kv* kv, int32_t ctx_len, int32_t max_len, int32_t* cand_staging,
+                    void* workspace_dev, void* stream, card_verify_result* out,
+                    int32_t* row_argmax_dev, card_step* step_host);
+int card_step_end(card_cache* cache, const card_step* step_host, const card_verify_result* out_host,
+                  int32_t flags, int32_t* emitted_host, int32_t* n_emitted_host);
+
 #ifdef __cplusplus
 }
 #endif

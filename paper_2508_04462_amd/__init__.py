@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     CardKV,
     CardVerifyResult,
     CardSampling,
+    CardStep,
+    CARD_STEP_NO_CORRECT,
     lib,
     lib_path,
     card_strerror,
@@ -31,6 +33,8 @@ from .binding import (  # noqa: F401
     card_verify,
     card_verify_debug_logits,
     card_verify_static,
+    card_step_begin,
+    card_step_end,
     card_verify_sampled,
     card_static_scratch_bytes,
     card_static_scratch_reset,

@@ -42,6 +42,13 @@ class CardSampling(C.Structure):
     _fields_ = [("temperature", C.c_float), ("seed", C.c_uint64)]
 
 
+class CardStep(C.Structure):
+    _fields_ = [("r", C.c_int32), ("hit", C.c_int32), ("path_score", C.c_float), ("cand", C.c_int32 * 32)]
+
+
+CARD_STEP_NO_CORRECT = 1
+
+
 class CardVerifyResult(C.Structure):
     _fields_ = [
         ("accepted_len", C.c_int32), ("correction_token", C.c_int32),
@@ -83,6 +90,10 @@ def _declare(lib: C.CDLL) -> C.CDLL:
     lib.card_verify.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P]
     lib.card_verify_sampled.restype = C.c_int
     lib.card_verify_sampled.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, C.POINTER(CardSampling), _P, _P, _P, _P, _P]
+    lib.card_step_begin.restype = C.c_int
+    lib.card_step_begin.argtypes = [_P, _cfgp, _P, _kvp, C.c_int32, C.c_int32, _P, _P, _P, _P, _P, C.POINTER(CardStep)]
+    lib.card_step_end.restype = C.c_int
+    lib.card_step_end.argtypes = [_P, C.POINTER(CardStep), _P, C.c_int32, _i32p, _i32p]
     lib.card_verify_static.restype = C.c_int
     lib.card_verify_static.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P]
     lib.card_static_scratch_bytes.restype = C.c_size_t
@@ -181,6 +192,21 @@ def card_verify_sampled(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: 
     return lib.card_verify_sampled(C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, _ptr(cand_dev), r,
                                    C.byref(sampling), _ptr(workspace_dev), _ptr(stream), _ptr(out_dev),
                                    _ptr(row_token_dev), _ptr(logits_dev))
+
+
+def card_step_begin(cache, cfg, packed_dev, kv: CardKV, ctx_len: int, max_len: int, cand_staging, workspace_dev,
+                    stream, out, row_argmax_dev, step: CardStep) -> int:
+    return lib.card_step_begin(cache, C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, max_len,
+                               _ptr(cand_staging), _ptr(workspace_dev), _ptr(stream), _ptr(out),
+                               _ptr(row_argmax_dev), C.byref(step))
+
+
+def card_step_end(cache, step: CardStep, out_host, flags: int = 0):
+    """Returns (status, [emitted tokens])."""
+    buf = (C.c_int32 * 33)()
+    n = C.c_int32(0)
+    st = lib.card_step_end(cache, C.byref(step), _ptr(out_host), flags, buf, C.byref(n))
+    return st, list(buf[: n.value])
 
 
 def card_verify_static(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: int, stream, out_dev,

@@ -340,6 +340,45 @@ int card_verify_sampled(const card_model_cfg* cfg, const void* packed_weights_de
                        row_token_dev, logits_dev, sampling);
 }
 
+int card_step_begin(card_cache* cache, const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
+                    int32_t ctx_len, int32_t max_len, int32_t* cand_staging, void* workspace_dev, void* stream,
+                    card_verify_result* out, int32_t* row_argmax_dev, card_step* step_host) {
+    if (!cache || !cfg || !kv || !cand_staging || !step_host) return CARD_EINVAL;
+    if (max_len < 1 || max_len > cfg->max_r || max_len > kMaxR) return CARD_ERANGE;
+    if (kv->pending_token < 0) return CARD_EINVAL;  // the query key is the token just verified
+    int32_t n = 0;
+    float score = 0.f;
+    const int hit = card_cache_query(cache, kv->pending_token, max_len, step_host->cand, &n, &score);
+    if (hit < 0) return hit;
+    if (hit == 0 || n < 1) {  // miss: a plain decode step on the verified token
+        n = 1;
+        step_host->cand[0] = kv->pending_token;
+    }
+    step_host->hit = hit > 0 ? 1 : 0;
+    step_host->r = n;
+    step_host->path_score = hit > 0 ? score : 0.f;
+    for (int i = 0; i < n; ++i) cand_staging[i] = step_host->cand[i];
+    return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_staging, n, workspace_dev, stream, out, row_argmax_dev,
+                       nullptr);
+}
+
+int card_step_end(card_cache* cache, const card_step* step_host, const card_verify_result* out_host, int32_t flags,
+                  int32_t* emitted_host, int32_t* n_emitted_host) {
+    if (!cache || !step_host || !out_host || !emitted_host || !n_emitted_host) return CARD_EINVAL;
+    const int a = out_host->accepted_len;
+    if (a < 1 || a > step_host->r) return CARD_EDEVICE;  // the step failed (or was not a CARD step)
+    // what the step has verified beyond the query key: the accepted part of the path, then the target's own token
+    int n = 0;
+    for (int i = 1; i < a; ++i) emitted_host[n++] = step_host->cand[i];
+    emitted_host[n++] = out_host->correction_token;
+    *n_emitted_host = n;
+    if (flags & CARD_STEP_NO_CORRECT) return CARD_OK;
+    // the accepted candidates (query key first) are walked down the tree: the children of the last
+    // one become level 0, where the next query looks the target's own token up
+    const int st = card_cache_correct(cache, step_host->cand, a);
+    return st < 0 ? st : CARD_OK;
+}
+
 int card_verify_static(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv, int32_t ctx_len,
                        const int32_t* cand_tokens_dev, int32_t r, void* stream, card_verify_result* out_dev,
                        int32_t* row_argmax_dev) {

@@ -186,3 +186,49 @@ def test_cache_concurrent_writer_and_reader_do_not_corrupt():
         stop.set()
         th.join()
     assert not errors
+
+
+def test_step_end_emits_and_corrects_on_the_host():
+    """card_step_end is host logic: accepted path tokens behind the query key, then the target's own
+    token; the cache is re-rooted at the accepted candidates unless the no-correct flag is set."""
+    import ctypes as C
+
+    def tree():
+        c = card.CandidateCache(K=4, max_depth=4)
+        c.write(0, [10], [-1], [1.0])
+        c.write(1, [11, 21], [0, 0], [0.9, 0.4])
+        c.write(2, [12, 22, 32], [0, 0, 1], [0.8, 0.3, 0.2])
+        return c
+
+    step = card.CardStep()
+    step.r, step.hit = 3, 1
+    step.cand[0], step.cand[1], step.cand[2] = 10, 11, 12
+    out = (C.c_int32 * 4)(2, 22, 100, 2)  # accepted the key and 11, the target's own next token is 22
+    c = tree()
+    st, toks = card.card_step_end(c.h, step, C.addressof(out), 0)
+    assert st == card.CARD_OK and toks == [11, 22]
+    n, t, p, s = c.level(0)  # level 0 now holds the children of node 11
+    assert sorted(t) == [12, 22]
+    hit, path, _ = c.query(22, 4)
+    assert hit and path == [22]
+    c2 = tree()
+    st, toks = card.card_step_end(c2.h, step, C.addressof(out), card.CARD_STEP_NO_CORRECT)
+    assert st == card.CARD_OK and toks == [11, 22]
+    assert c2.level(0)[1] == [10] and c2.depth() == 3  # untouched
+    bad = (C.c_int32 * 4)(-1, -1, 100, 0)  # a failed step must not touch the cache
+    st, toks = card.card_step_end(c2.h, step, C.addressof(bad), 0)
+    assert st == card.CARD_EDEVICE and c2.level(0)[1] == [10]
+    over = (C.c_int32 * 4)(4, 5, 100, 4)  # more accepted than forwarded
+    assert card.card_step_end(c2.h, step, C.addressof(over), 0)[0] == card.CARD_EDEVICE
+
+
+def test_step_begin_argument_errors():
+    cfg = card.make_cfg(ci.SHAPES["tiny"], 256, max_r=8)
+    c = card.CandidateCache(K=4, max_depth=4)
+    step = card.CardStep()
+    kv = card.CardKV(0x1000, 0x1000, 0x1000, 16, 5)
+    assert card.card_step_begin(c.h, cfg, 0x1000, kv, 0, 0, 0x1000, 0x1000, None, 0x1000, None, step) == card.CARD_ERANGE
+    assert card.card_step_begin(c.h, cfg, 0x1000, kv, 0, 9, 0x1000, 0x1000, None, 0x1000, None, step) == card.CARD_ERANGE
+    no_pending = card.CardKV(0x1000, 0x1000, 0x1000, 16, -1)
+    assert card.card_step_begin(c.h, cfg, 0x1000, no_pending, 0, 4, 0x1000, 0x1000, None, 0x1000, None, step) == card.CARD_EINVAL
+    assert card.card_step_begin(None, cfg, 0x1000, kv, 0, 4, 0x1000, 0x1000, None, 0x1000, None, step) == card.CARD_EINVAL

@@ -113,3 +113,65 @@ def test_cache_miss_is_a_plain_decode_step():
         ref = co.verify(shape, w, kv_ref, shape.ctx, g0, [g0], keep_logits=True)
         if ref.row_gap[0] > GAP:
             assert res["correction_token"] == ref.correction_token
+
+
+@pytest.mark.parametrize("flags,p,seed", [(0, 0.6, 33), (0, 0.9, 42), (1, 0.6, 33)], ids=["correct-0.6", "correct-0.9", "query-without-correct"])
+def test_step_calls_variable_paths_miss_fallback_and_the_no_correct_variant(flags, p, seed):
+    """card_step_begin / card_step_end: one call queries the cache and enqueues the step with
+    whatever path length the cache holds (a miss degrades to r = 1 inside the same call), the
+    other emits the tokens and corrects the cache - or, with CARD_STEP_NO_CORRECT, leaves it alone
+    (the ablation's "query without correct").  The draft writes a fresh tree only every other
+    step, paths have ragged lengths, so hits on the sibling branch, hits on a stale tree and
+    misses all occur; the text must be the oracle's greedy text whatever happens."""
+    import torch
+
+    import paper_2508_04462_amd as card
+
+    shape, n_new, r = TINY, 24, 6
+    tgt, w = make_pair(shape, seed, max_ctx=shape.ctx + n_new + r + 16)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, shape.ctx, shape.vocab).tolist()
+    kv_ref = co.OracleKV.empty(shape, shape.ctx + n_new + r + 16)
+    g0 = co.prefill(shape, w, kv_ref, ctx)
+    want, gaps = co.greedy_decode_cached(shape, w, kv_ref, shape.ctx, g0, n_new)
+    decisive_upto = next((i for i, g in enumerate(gaps) if g <= GAP), n_new)
+    truth = want[: decisive_upto + 1]
+    if len(truth) < 4:
+        pytest.skip("seed without a decisive prefix")
+    tgt.prefill(ctx)
+    cache = card.CandidateCache(K=8, max_depth=r)
+    rng = np.random.default_rng(seed)
+    staging = torch.zeros(32, dtype=torch.int32).pin_memory()
+    out = torch.zeros(4, dtype=torch.int32).pin_memory()
+    step = card.CardStep()
+    n, pending, emitted = shape.ctx, g0, [g0]
+    hits = misses = 0
+    lens = set()
+    it = 0
+    while len(emitted) < len(truth):
+        e = len(emitted) - 1
+        if it % 2 == 0:  # the draft keeps up only every other step
+            depth = 2 + it % (r - 1)  # ragged path lengths
+            _draft(cache, truth[e:] + [0] * r, rng, p, depth, 4)
+        it += 1
+        st = card.card_step_begin(cache.h, tgt.cfg, tgt.packed, tgt.kv(pending), n, r, staging, tgt.workspace,
+                                  tgt._stream(), out, tgt.row_argmax, step)
+        assert st == card.CARD_OK, card.card_strerror(st)
+        torch.cuda.current_stream().synchronize()
+        assert 1 <= step.r <= r and step.cand[0] == pending
+        hits += step.hit
+        misses += 1 - step.hit
+        if not step.hit:
+            assert step.r == 1
+        lens.add(step.r)
+        acc, corr, first, count = out.tolist()
+        assert 1 <= acc <= step.r and (first, count) == (n, acc)
+        st, toks = card.card_step_end(cache.h, step, out, flags)
+        assert st == card.CARD_OK and toks == list(step.cand[1:acc]) + [corr]
+        emitted += toks
+        n += acc
+        pending = corr
+    k = min(len(emitted), len(truth))
+    assert emitted[:k] == truth[:k]
+    assert hits >= 1 and len(lens) >= 2
+    if flags:  # never corrected: the tree the draft wrote stays as written until the next draft
+        assert cache.depth() >= 1
