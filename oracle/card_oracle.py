@@ -167,6 +167,62 @@ def forward_rows(
     return y @ w.lm_head.astype(dtype).T
 
 
+def forward_tree_rows(
+    cfg, w: OracleWeights, kv: OracleKV, tokens: Sequence[int], positions: Sequence[int], slots: Sequence[int],
+    visible: Sequence[Sequence[int]], dtype=np.float64,
+) -> np.ndarray:
+    """Draft-side forward over tree nodes (Cache Construction, eq. (1): the draft decodes the K
+    sequences of the primary cache in one pass; Mask Construction for Draft Model).  Row i carries
+    token tokens[i] at sequence position positions[i] (context length + depth of the node); its key
+    and value go to cache slot slots[i]; it attends to the cache slots visible[i] - the committed
+    context, the node's ancestors and the node itself, never its peers - which must include
+    slots[i].  Rows of one call do not see each other unless listed.  Returns logits [rows, vocab]."""
+    r = len(tokens)
+    x = np.stack([w.embed[int(t)].astype(dtype) for t in tokens])
+    hq, hkv, h = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    for l in range(cfg.n_layers):
+        wl = w.layer(l)
+        u = rmsnorm(x, wl["g_attn"].astype(dtype), dtype(cfg.rms_eps))
+        q = u @ wl["wq"].astype(dtype).T
+        k = u @ wl["wk"].astype(dtype).T
+        v = u @ wl["wv"].astype(dtype).T
+        for i in range(r):  # every row's key and value are stored before any row attends
+            kv.k[l][slots[i]] = cache_value(rope(k[i].reshape(hkv, h), positions[i], cfg.rope_theta), kv.store)
+            kv.v[l][slots[i]] = cache_value(v[i].reshape(hkv, h), kv.store)
+        att = np.empty((r, hq * h), dtype)
+        for i in range(r):
+            assert slots[i] in visible[i]
+            vis = np.asarray(sorted(visible[i]), dtype=np.int64)
+            qi = rope(q[i].reshape(hq, h), positions[i], cfg.rope_theta)
+            att[i] = attend_row(cfg, qi, kv.k[l][vis], kv.v[l][vis]).reshape(-1)
+        x = x + att @ wl["wo"].astype(dtype).T
+        u2 = rmsnorm(x, wl["g_ffn"].astype(dtype), dtype(cfg.rms_eps))
+        gate = u2 @ wl["wg"].astype(dtype).T
+        up = u2 @ wl["wu"].astype(dtype).T
+        x = x + (silu(gate) * up) @ wl["wd"].astype(dtype).T
+    y = rmsnorm(x, w.g_final.astype(dtype), dtype(cfg.rms_eps))
+    return y @ w.lm_head.astype(dtype).T
+
+
+def softmax_rows(logits: np.ndarray) -> np.ndarray:
+    """Row-wise softmax: the distributions P_i of eq. (1)."""
+    z = logits - logits.max(axis=-1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def topk_rows(probs: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. (2): per row the k most probable tokens and their probabilities, most probable first;
+    equal probabilities in ascending token order."""
+    toks = np.empty((probs.shape[0], k), dtype=np.int64)
+    vals = np.empty((probs.shape[0], k), dtype=probs.dtype)
+    for i, row in enumerate(probs):
+        order = sorted(range(row.shape[0]), key=lambda t: (-row[t], t))[:k]
+        toks[i] = order
+        vals[i] = row[order]
+    return toks, vals
+
+
 def prefill(cfg, w, kv, ctx_tokens: Sequence[int], dtype=np.float64, chunk: int = 64) -> int:
     """Fill kv[0:n) from the context and return the pending prediction g0 = arg-max of the
     last context row."""
