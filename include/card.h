@@ -304,6 +304,60 @@ int card_cache_read_level(const card_cache* c, int32_t level, int32_t* tokens, i
                           float* path_score);
 
 /* ------------------------------------------------------------------------------------------
+ * Draft side: construction of one cache level on the device (Cache Construction, eqs. (1)-(9);
+ * Mask Construction for Draft Model).  The draft model - any model in the same packed format -
+ * forwards the nodes of the primary cache's current level in one pass and expands each into its
+ * k most probable next tokens; the K best-scored extensions form the next level.
+ *
+ * card_draft_level, eqs. (1)-(2): forwards n_rows <= max_r tree nodes.  Row i carries token
+ * tokens_dev[i] at sequence position positions_dev[i] (context length + depth of the node); its
+ * key and value are stored in cache slot first_slot + i (slots of tree nodes lie behind the
+ * committed context: first_slot >= ctx_len).  Visibility (the mask rules: a node inherits its
+ * parent's causal history and sees itself, never its peers): every slot below mask_base is
+ * visible; slot mask_base + j is visible to row i iff bit j % 32 of mask_dev[i * mask_words + j / 32]
+ * is set.  mask_base is a multiple of 16, at most ctx_len (bits of context slots at or above
+ * mask_base must be set by the caller); first_slot + n_rows <= mask_base + 32 * mask_words;
+ * mask_words <= 32 (1024 tree slots).  A level wider than max_r rows is forwarded in several
+ * calls (peers do not see each other, so the calls are independent).  Results, without the
+ * logits ever being stored: per row the k <= 16 most probable tokens (most probable first, equal
+ * logits by ascending token id) and their probabilities under softmax over the whole vocabulary.
+ * logits_dev (optional, test use): fp32 [n_rows][vocab].  Errors as card_verify.
+ *
+ * card_cache_select, eqs. (3)-(7): scores every (parent i, its j-th token) pair
+ * w = prob[i][j] * sigma[i] (sigma: cumulative probability of parent i's sequence, eq. (4)),
+ * pools the n_parents * k tuples (eq. (5)), sorts them by score (eq. (6)) and keeps the K best
+ * (eq. (7)): out_tokens / out_scores / out_parents [K], best first, equal scores by (parent, rank).
+ * n_parents * k <= 2048.  Entries of topk_tokens_dev that are negative are skipped.  Returns the
+ * number of tuples written, min(K, n_parents * k), or a negative status.  Appending token m to
+ * parent m's sequence (eqs. (8)-(9)) is what card_cache_write stores from these arrays.
+ * ---------------------------------------------------------------------------------------- */
+/* Host helper, Mask Construction for Draft Model: the mask rows of one level from the rows of
+ * the level above.  Row i = row parent_idx_host[i] of parent_mask_host (inherited causal history;
+ * parent -1: a root, which sees only the context slots in [mask_base, ctx_len)) plus the bit of
+ * its own slot first_slot + i.  Arrays are host memory, [rows][mask_words]. */
+int card_tree_mask_level(const uint32_t* parent_mask_host, const int32_t* parent_idx_host,
+                         int32_t n_rows, int32_t first_slot, int32_t ctx_len, int32_t mask_base,
+                         int32_t mask_words, uint32_t* out_mask_host);
+
+typedef struct card_tree_rows {
+    const int32_t* tokens_dev;     /* [n_rows] */
+    const int32_t* positions_dev;  /* [n_rows] */
+    int32_t first_slot;
+    const uint32_t* mask_dev;      /* [n_rows][mask_words] */
+    int32_t mask_words;
+    int32_t mask_base;
+} card_tree_rows;
+
+int card_draft_level(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
+                     int32_t ctx_len, const card_tree_rows* rows, int32_t n_rows, int32_t k,
+                     void* workspace_dev, void* stream, int32_t* topk_tokens_dev,
+                     float* topk_probs_dev, float* logits_dev);
+int card_cache_select(const float* sigma_dev, const int32_t* topk_tokens_dev,
+                      const float* topk_probs_dev, int32_t n_parents, int32_t k, int32_t K,
+                      int32_t* out_tokens_dev, float* out_scores_dev, int32_t* out_parents_dev,
+                      void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * One target step of the query-and-correct loop in two calls (overview figure: query the cache
  * with the token just verified, verify the returned path, correct the cache with what was
  * verified; Comparing with Tree-Verified Methods: the number of verified tokens varies from step

@@ -42,6 +42,11 @@ class CardSampling(C.Structure):
     _fields_ = [("temperature", C.c_float), ("seed", C.c_uint64)]
 
 
+class CardTreeRows(C.Structure):
+    _fields_ = [("tokens_dev", C.c_void_p), ("positions_dev", C.c_void_p), ("first_slot", C.c_int32),
+                ("mask_dev", C.c_void_p), ("mask_words", C.c_int32), ("mask_base", C.c_int32)]
+
+
 class CardStep(C.Structure):
     _fields_ = [("r", C.c_int32), ("hit", C.c_int32), ("path_score", C.c_float), ("cand", C.c_int32 * 32)]
 
@@ -90,6 +95,12 @@ def _declare(lib: C.CDLL) -> C.CDLL:
     lib.card_verify.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, _P, _P, _P, _P]
     lib.card_verify_sampled.restype = C.c_int
     lib.card_verify_sampled.argtypes = [_cfgp, _P, _kvp, C.c_int32, _P, C.c_int32, C.POINTER(CardSampling), _P, _P, _P, _P, _P]
+    lib.card_draft_level.restype = C.c_int
+    lib.card_draft_level.argtypes = [_cfgp, _P, _kvp, C.c_int32, C.POINTER(CardTreeRows), C.c_int32, C.c_int32, _P, _P, _P, _P, _P]
+    lib.card_tree_mask_level.restype = C.c_int
+    lib.card_tree_mask_level.argtypes = [_P, _i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P]
+    lib.card_cache_select.restype = C.c_int
+    lib.card_cache_select.argtypes = [_P, _P, _P, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P, _P]
     lib.card_step_begin.restype = C.c_int
     lib.card_step_begin.argtypes = [_P, _cfgp, _P, _kvp, C.c_int32, C.c_int32, _P, _P, _P, _P, _P, C.POINTER(CardStep)]
     lib.card_step_end.restype = C.c_int
@@ -192,6 +203,31 @@ def card_verify_sampled(cfg, packed_dev, kv: CardKV, ctx_len: int, cand_dev, r: 
     return lib.card_verify_sampled(C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, _ptr(cand_dev), r,
                                    C.byref(sampling), _ptr(workspace_dev), _ptr(stream), _ptr(out_dev),
                                    _ptr(row_token_dev), _ptr(logits_dev))
+
+
+def card_draft_level(cfg, packed_dev, kv: CardKV, ctx_len: int, rows: CardTreeRows, n_rows: int, k: int,
+                     workspace_dev, stream, topk_tokens_dev, topk_probs_dev, logits_dev=None) -> int:
+    return lib.card_draft_level(C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, C.byref(rows), n_rows, k,
+                                _ptr(workspace_dev), _ptr(stream), _ptr(topk_tokens_dev), _ptr(topk_probs_dev),
+                                _ptr(logits_dev))
+
+
+def card_tree_mask_level(parent_mask, parent_idx, first_slot: int, ctx_len: int, mask_base: int, mask_words: int):
+    """parent_mask: list of rows (lists of mask_words uint32) or None; returns (status, rows)."""
+    n = len(parent_idx)
+    out = (C.c_uint32 * (n * mask_words))()
+    pm = None
+    if parent_mask is not None:
+        flat = [int(w) for row in parent_mask for w in row]
+        pm = (C.c_uint32 * len(flat))(*flat)
+    st = lib.card_tree_mask_level(pm, _i32(parent_idx), n, first_slot, ctx_len, mask_base, mask_words, out)
+    return st, [list(out[i * mask_words:(i + 1) * mask_words]) for i in range(n)]
+
+
+def card_cache_select(sigma_dev, topk_tokens_dev, topk_probs_dev, n_parents: int, k: int, K: int, out_tokens_dev,
+                      out_scores_dev, out_parents_dev, stream=None) -> int:
+    return lib.card_cache_select(_ptr(sigma_dev), _ptr(topk_tokens_dev), _ptr(topk_probs_dev), n_parents, k, K,
+                                 _ptr(out_tokens_dev), _ptr(out_scores_dev), _ptr(out_parents_dev), _ptr(stream))
 
 
 def card_step_begin(cache, cfg, packed_dev, kv: CardKV, ctx_len: int, max_len: int, cand_staging, workspace_dev,

@@ -127,11 +127,23 @@ struct StaticWs {
 StaticWs g_static[kMaxDevices];
 std::mutex g_static_mu;
 
+// Draft-side options of a step (card_draft_level): tree rows and the per-row top-k.
+struct TreeOpt {
+    const int32_t* row_pos;
+    int32_t first_slot;
+    const uint32_t* mask;
+    int32_t mask_words, mask_base;
+    int32_t topk;
+    int32_t* topk_tok;
+    float* topk_prob;
+};
+
 // One persistent kernel runs the whole step (card_verify.hip).
 int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv, int32_t ctx_len,
                 const int32_t* cand, int32_t r, void* workspace, void* stream, card_verify_result* out,
-                int32_t* row_argmax, float* logits, const card_sampling* sampling = nullptr) {
-    if (!cfg || !packed || !kv || !cand || !workspace || !out) return CARD_EINVAL;
+                int32_t* row_argmax, float* logits, const card_sampling* sampling = nullptr,
+                const TreeOpt* tree = nullptr) {
+    if (!cfg || !packed || !kv || !cand || !workspace || (!out && !tree)) return CARD_EINVAL;
     const Layout L = make_layout(cfg);
     if (!L.ok) return CARD_EINVAL;
     if (!kv->k_pages || !kv->v_pages || !kv->block_table || kv->n_pages <= 0) return CARD_EINVAL;
@@ -139,7 +151,14 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     if (size_t(kv->n_pages) * cfg->n_kv_heads * 16 * cfg->head_dim * 2 >= (size_t(1) << 32)) return CARD_EINVAL;
     if (r < 1 || r > cfg->max_r) return CARD_ERANGE;
     if (ctx_len < 0) return CARD_EINVAL;
-    if (int64_t(ctx_len) + r > cfg->max_ctx) return CARD_ECAPACITY;
+    const int32_t slot0 = tree ? tree->first_slot : ctx_len;
+    if (int64_t(slot0) + r > cfg->max_ctx) return CARD_ECAPACITY;
+    if (tree) {
+        if (!tree->row_pos || !tree->mask || !tree->topk_tok || !tree->topk_prob) return CARD_EINVAL;
+        if (tree->mask_words < 1 || tree->mask_words > 32 || tree->topk < 1 || tree->topk > 16) return CARD_ERANGE;
+        if (tree->mask_base < 0 || tree->mask_base % kKvBlock || tree->mask_base > ctx_len) return CARD_EINVAL;
+        if (slot0 < ctx_len || int64_t(slot0) + r > int64_t(tree->mask_base) + 32 * tree->mask_words) return CARD_ERANGE;
+    }
     const int cus = grid_size(cfg);
     if (cus <= 0) return CARD_EDEVICE;
 
@@ -180,7 +199,9 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.vpool = static_cast<__bf16*>(kv->v_pages);
     a.pool_layer_elems = size_t(kv->n_pages) * cfg->n_kv_heads * 16 * h;
     a.block_table = kv->block_table;
-    a.pages_used = ceil_div(ctx_len + r, kKvBlock);
+    a.pages_used = ceil_div(slot0 + r, kKvBlock);
+    a.slot0 = slot0;
+    a.old_end = tree ? tree->mask_base : ctx_len;
     a.row_tiles = ceil_div(a.G * r, 16);
     // Cut the context so that a workgroup's share fits the page buffers of its wavefronts (all of
     // its old-context pages are then in flight before the barrier in front of attention), as long
@@ -209,6 +230,18 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.acount = reinterpret_cast<uint32_t*>(ws + L.m_acount_off);
     a.flags = reinterpret_cast<uint32_t*>(ws + L.m_flags_off);
     a.cand = cand;
+    if (tree) {
+        a.row_pos = tree->row_pos;
+        a.tmask = tree->mask;
+        a.tmask_words = tree->mask_words;
+        a.tmask_base = tree->mask_base;
+        a.topk = tree->topk;
+        a.topk_tok = tree->topk_tok;
+        a.topk_prob = tree->topk_prob;
+        a.topk_part = reinterpret_cast<unsigned long long*>(ws + L.m_topk_off);
+        a.lse_part = reinterpret_cast<float*>(ws + L.m_lse_off);
+        if (!out) out = reinterpret_cast<card_verify_result*>(ws + L.m_out_off);
+    }
     a.pending = kv->pending_token;
     if (sampling && sampling->temperature > 0.f) {
         a.inv_temp = 1.0f / sampling->temperature;
@@ -338,6 +371,57 @@ int card_verify_sampled(const card_model_cfg* cfg, const void* packed_weights_de
     if (!sampling || !(sampling->temperature >= 0.f)) return CARD_EINVAL;
     return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_tokens_dev, r, workspace_dev, stream, out_dev,
                        row_token_dev, logits_dev, sampling);
+}
+
+int card_draft_level(const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv, int32_t ctx_len,
+                     const card_tree_rows* rows, int32_t n_rows, int32_t k, void* workspace_dev, void* stream,
+                     int32_t* topk_tokens_dev, float* topk_probs_dev, float* logits_dev) {
+    if (!rows) return CARD_EINVAL;
+    TreeOpt t = {rows->positions_dev, rows->first_slot, rows->mask_dev, rows->mask_words, rows->mask_base, k,
+                 topk_tokens_dev, topk_probs_dev};
+    card_kv kv2;
+    if (!kv) return CARD_EINVAL;
+    kv2 = *kv;
+    kv2.pending_token = -1;
+    return verify_impl(cfg, packed_weights_dev, &kv2, ctx_len, rows->tokens_dev, n_rows, workspace_dev, stream, nullptr,
+                       nullptr, logits_dev, nullptr, &t);
+}
+
+int card_tree_mask_level(const uint32_t* parent_mask_host, const int32_t* parent_idx_host, int32_t n_rows,
+                         int32_t first_slot, int32_t ctx_len, int32_t mask_base, int32_t mask_words,
+                         uint32_t* out_mask_host) {
+    if (!parent_idx_host || !out_mask_host || n_rows < 1) return CARD_EINVAL;
+    if (mask_words < 1 || mask_words > 32 || mask_base < 0 || mask_base % kKvBlock || mask_base > ctx_len) return CARD_EINVAL;
+    if (first_slot < ctx_len || int64_t(first_slot) + n_rows > int64_t(mask_base) + 32 * mask_words) return CARD_ERANGE;
+    for (int i = 0; i < n_rows; ++i) {
+        uint32_t* row = out_mask_host + size_t(i) * mask_words;
+        const int p = parent_idx_host[i];
+        if (p >= 0) {
+            if (!parent_mask_host) return CARD_EINVAL;
+            // inherit the parent's causal history
+            for (int w = 0; w < mask_words; ++w) row[w] = parent_mask_host[size_t(p) * mask_words + w];
+        } else {
+            // a root of the tree sees the committed context only
+            for (int w = 0; w < mask_words; ++w) row[w] = 0u;
+            for (int s = mask_base; s < ctx_len; ++s) row[(s - mask_base) >> 5] |= 1u << ((s - mask_base) & 31);
+        }
+        const int own = first_slot + i - mask_base;  // ... plus the node itself; peers stay invisible
+        row[own >> 5] |= 1u << (own & 31);
+    }
+    return CARD_OK;
+}
+
+int card_cache_select(const float* sigma_dev, const int32_t* topk_tokens_dev, const float* topk_probs_dev, int32_t n_parents,
+                      int32_t k, int32_t K, int32_t* out_tokens_dev, float* out_scores_dev, int32_t* out_parents_dev,
+                      void* stream) {
+    if (!sigma_dev || !topk_tokens_dev || !topk_probs_dev || !out_tokens_dev || !out_scores_dev || !out_parents_dev)
+        return CARD_EINVAL;
+    if (n_parents < 1 || k < 1 || k > 16 || K < 1 || int64_t(n_parents) * k > 256 * kSelPerThread) return CARD_ERANGE;
+    SelectArgs a = {sigma_dev, topk_tokens_dev, topk_probs_dev, n_parents, k, K, out_tokens_dev, out_scores_dev,
+                    out_parents_dev};
+    hipLaunchKernelGGL(k_cache_select, dim3(1), dim3(256), 0, as_stream(stream), a);
+    const int st = launch_status();
+    return st != CARD_OK ? st : (K < n_parents * k ? K : n_parents * k);
 }
 
 int card_step_begin(card_cache* cache, const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,

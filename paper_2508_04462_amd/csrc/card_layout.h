@@ -77,7 +77,7 @@ struct Layout {
     size_t ws_bytes;
     // workspace of the persistent kernel (byte offsets) and strides in elements
     size_t m_xres_off, m_xfrag_off, m_ss_off, m_qfrag_off, m_attfrag_off, m_actfrag_off, m_apart_off, m_bar_off,
-        m_acount_off, m_flags_off, m_best_off, m_rope_off;
+        m_acount_off, m_flags_off, m_best_off, m_rope_off, m_topk_off, m_lse_off, m_out_off;
     size_t xfrag_stride, attfrag_stride, actfrag_stride, qfrag_stride;
     int32_t m_attn_max_splits;
 };
@@ -175,6 +175,9 @@ inline Layout make_layout(const card_model_cfg* c) {
     L.m_acount_off = take(size_t(c->n_kv_heads) * (2 * G) * 4);
     L.m_best_off = take(size_t(kMaxR) * 8);
     L.m_rope_off = take(size_t(kMaxR) * h * 4);
+    L.m_topk_off = take(size_t(256) * kMaxR * 16 * 8);  // per workgroup and row: sixteen best keys
+    L.m_lse_off = take(size_t(256) * kMaxR * 2 * 4);    // per workgroup and row: (max, sum of exp)
+    L.m_out_off = take(64);                             // where a draft-side call parks the verify result
     L.ws_bytes = w;
     L.ok = true;
     return L;

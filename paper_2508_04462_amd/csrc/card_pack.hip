@@ -56,6 +56,69 @@ __global__ __launch_bounds__(256) void k_ws_init(uint4v* ws, size_t n16, uint32_
     if (mi % stride == size_t(blockIdx.x) * 256 + threadIdx.x) *magic_word = kWsMagic;
 }
 
+// Cache construction, eqs. (3)-(7): score every (parent, top-k token) pair w = p * sigma(parent),
+// pool the M * k tuples and keep the K best, best first; equal scores in (parent, rank) order.  One
+// workgroup: M * k <= 256 * kSelPerThread elements, K rounds of "largest key in the workgroup".
+constexpr int kSelPerThread = 8;
+struct SelectArgs {
+    const float* sigma;     // [M] cumulative probability of each parent sequence, eq. (4)
+    const int32_t* tok;     // [M][k] eq. (2)
+    const float* prob;      // [M][k]
+    int32_t M, k, K;
+    int32_t* out_tok;       // [K]
+    float* out_score;       // [K] eq. (3)
+    int32_t* out_parent;    // [K]
+};
+
+__global__ __launch_bounds__(256) void k_cache_select(SelectArgs a) {
+    __shared__ unsigned long long wbest[2][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int total = a.M * a.k;
+    unsigned long long mine[kSelPerThread];
+#pragma unroll
+    for (int e = 0; e < kSelPerThread; ++e) {
+        const int flat = tid + e * 256;
+        mine[e] = 0ull;
+        if (flat < total && a.tok[flat] >= 0) {
+            const float w = a.prob[flat] * a.sigma[flat / a.k];
+            // non-negative floats order like their bit patterns; +1 keeps a zero score above "empty"
+            mine[e] = ((static_cast<unsigned long long>(__float_as_uint(w)) + 1ull) << 32) | (0xffffffffu - uint32_t(flat));
+        }
+    }
+    const int n_out = a.K < total ? a.K : total;
+    for (int j = 0; j < n_out; ++j) {
+        unsigned long long best = 0ull;
+#pragma unroll
+        for (int e = 0; e < kSelPerThread; ++e) best = mine[e] > best ? mine[e] : best;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long other = __shfl_xor(best, o);
+            best = other > best ? other : best;
+        }
+        if (lane == 0) wbest[j & 1][wave] = best;
+        __syncthreads();
+        best = wbest[j & 1][0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) best = wbest[j & 1][w] > best ? wbest[j & 1][w] : best;
+        if (best != 0ull) {
+#pragma unroll
+            for (int e = 0; e < kSelPerThread; ++e) mine[e] = mine[e] == best ? 0ull : mine[e];
+        }
+        if (tid == 0) {
+            if (best != 0ull) {
+                const int flat = int(0xffffffffu - uint32_t(best & 0xffffffffull));
+                a.out_tok[j] = a.tok[flat];
+                a.out_score[j] = __uint_as_float(uint32_t((best >> 32) - 1ull));
+                a.out_parent[j] = flat / a.k;
+            } else {
+                a.out_tok[j] = -1;
+                a.out_score[j] = 0.f;
+                a.out_parent[j] = -1;
+            }
+        }
+    }
+}
+
 struct GatherArgs {
     const __bf16* kpool;
     const __bf16* vpool;

@@ -76,6 +76,19 @@ struct MegaArgs {
     uint32_t* flags;   // [kFlagCopies][256] last barrier sequence number each workgroup has reached
     uint32_t* acount;  // [Hkv * row_tiles] arrival counters of the attention cuts; zero between uses
     const int32_t* cand;
+    // draft-side tree rows (all zero / null for a verification step): row m sits at sequence position
+    // row_pos[m] and in cache slot slot0 + m; it sees every slot below tmask_base and, from there on,
+    // the slots whose bit is set in its mask row tmask[m * tmask_words ..]
+    int32_t slot0, old_end;       // slot of row 0; slots below old_end hold context written by earlier calls
+    const int32_t* row_pos;
+    const uint32_t* tmask;
+    int32_t tmask_words, tmask_base;
+    // per-row top-k of the vocabulary phase instead of the arg-max (topk = 0: arg-max)
+    int32_t topk;
+    unsigned long long* topk_part;  // [nwg][kMaxR][16] best keys of each workgroup's columns
+    float* lse_part;                // [nwg][kMaxR][2]  (max, sum of exp) of each workgroup's columns
+    int32_t* topk_tok;              // out [r][topk]
+    float* topk_prob;               // out [r][topk]
     int32_t pending;
     float inv_temp;          // 0: greedy (arg-max of the logits); > 0: sample, logits / temperature + Gumbel noise
     uint32_t seed_lo, seed_hi;
@@ -417,6 +430,13 @@ __device__ __forceinline__ float gumbel_noise(uint32_t row_key, uint32_t token) 
 
 enum MegaEpi { ME_QKV = 0, ME_RESID = 1, ME_SWIGLU = 2, ME_LM = 3 };
 
+// Running state of one thread across the batches of the vocabulary phase when the phase keeps a
+// per-row top-k and a log-sum-exp (draft side) instead of the arg-max.
+struct LmState {
+    unsigned long long run[2];  // this lane's share of its row's sixteen best keys so far
+    float m, s;                 // running maximum and sum of exp(value - m) over this lane's columns
+};
+
 struct EpiArgs {
     int32_t layer;
     int32_t ts0;  // timeline slots of this phase: ts0 first activations in, ts0+1 k-loop left, ts0+2 ticks spent waiting for fragments; <= 0: none
@@ -433,6 +453,8 @@ struct EpiArgs {
     __bf16* vpool;
     // SWIGLU
     __bf16* actfrag;
+    // LM with top-k
+    LmState* lm;
 };
 
 struct NoHook {
@@ -728,6 +750,66 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                     if (i < nvalid_s && n < a.V) a.logits[size_t(m) * a.V + n] = sm.tile[nl * COLS + m] * sm.row_scale[m];
                 }
             }
+            if (a.topk > 0) {
+                // Draft side (Cache Construction, eqs. (1)-(2)): per row the k most probable tokens and
+                // the log-sum-exp that turns their logits into probabilities, without storing the
+                // row.  The lanes of a row are consecutive (16 of them with one row tile, 8 with
+                // two), each owns eight columns of the batch and a share of the row's running best
+                // sixteen; sixteen rounds of "largest key among the row's lanes" rebuild that list
+                // from the old list and the new columns.  Keys are (ordered logit, ~token): unique,
+                // so the lane that holds a round's winner knows it and drops it.
+                constexpr int LPR = kMegaThreads / COLS, CPL = NBS * 16 / LPR, RUN = 16 / LPR;
+                static_assert(CPL == 8 && RUN * LPR == 16, "eight columns per lane, sixteen entries per row");
+                LmState& lm = *ea.lm;
+                const int m = tid / LPR, p = tid % LPR;
+                const float sc = m < r ? sm.row_scale[m] : 0.f;
+                unsigned long long cand[CPL];
+#pragma unroll
+                for (int q = 0; q < CPL; ++q) {
+                    const int nl = p * CPL + q, i = nl >> 4;
+                    const int n = (tile0 + i * a.nwg) * 16 + (nl & 15);
+                    cand[q] = 0ull;
+                    if (m < r && i < nvalid_s && n < a.V) {
+                        const float val = sm.tile[nl * COLS + m] * sc;
+                        cand[q] = (static_cast<unsigned long long>(float_key(val)) << 32) | (0xffffffffu - uint32_t(n));
+                        if (val > lm.m) {
+                            lm.s = lm.s * __expf(lm.m - val) + 1.f;
+                            lm.m = val;
+                        } else {
+                            lm.s += __expf(val - lm.m);
+                        }
+                    }
+                }
+                unsigned long long nr[RUN];
+#pragma unroll
+                for (int u = 0; u < RUN; ++u) nr[u] = 0ull;
+#pragma unroll 1
+                for (int j = 0; j < 16; ++j) {
+                    unsigned long long loc = 0ull;
+#pragma unroll
+                    for (int q = 0; q < CPL; ++q) loc = cand[q] > loc ? cand[q] : loc;
+#pragma unroll
+                    for (int u = 0; u < RUN; ++u) loc = lm.run[u] > loc ? lm.run[u] : loc;
+                    unsigned long long best = loc;
+#pragma unroll
+                    for (int o = 1; o < LPR; o <<= 1) {
+                        const unsigned long long other = __shfl_xor(best, o);
+                        best = other > best ? other : best;
+                    }
+                    if (best != 0ull) {
+#pragma unroll
+                        for (int q = 0; q < CPL; ++q) cand[q] = cand[q] == best ? 0ull : cand[q];
+#pragma unroll
+                        for (int u = 0; u < RUN; ++u) lm.run[u] = lm.run[u] == best ? 0ull : lm.run[u];
+                    }
+                    if (p == j % LPR) {
+#pragma unroll
+                        for (int u = 0; u < RUN; ++u) nr[u] = (j / LPR == u) ? best : nr[u];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < RUN; ++u) lm.run[u] = nr[u];
+            }
             constexpr int PARTS = kMegaThreads / COLS;
             constexpr int ROWS_PER = NBS * 16 / PARTS;
             static_assert(ROWS_PER >= 1, "rows per thread");
@@ -771,7 +853,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                 const int h = a.h, half = h >> 1;
                 const int prow = (tile0 + i * a.nwg) * 16;
                 const float sc = sm.row_scale[m];
-                const int slot = a.ctx_len + m;
+                const int slot = a.slot0 + m;
                 const int page = a.block_table[slot >> 4], tk = slot & 15;
                 if (prow < a.qd + a.kvd) {
                     const bool is_q = prow < a.qd;
@@ -812,7 +894,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                 const int head = rel / h, jg = rel % h;
                 int m2 = 0;
                 while (m2 < r) {
-                    const int slot = a.ctx_len + m2;
+                    const int slot = a.slot0 + m2;
                     const int page = a.block_table[slot >> 4], tk = slot & 15;
                     const int run = min(r - m2, 16 - tk);
                     const size_t vb = (size_t(page) * a.Hkv + head) * (16 * h);
@@ -1063,7 +1145,7 @@ __device__ __forceinline__ void attn_preload(const MegaArgs& a, int layer, int w
 #pragma unroll
     for (int i = 0; i < NBUF; ++i) {
         const int pg = t.pg0 + wave + i * kMegaWaves;
-        loaded[i] = pg < t.pg1 && (pg + 1) * 16 <= a.ctx_len;
+        loaded[i] = pg < t.pg1 && (pg + 1) * 16 <= a.old_end;
         if (loaded[i]) attn_load_page<H>(a, kpool, vpool, t.kvh, pid[i], lane, bf.k[i], bf.v[i]);
     }
 }
@@ -1101,7 +1183,9 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
         const int rho = rt * 16 + col;
         const bool row_ok = rho < R;
         const int mrow = row_ok ? rho / a.G : -1;
-        const int limit = a.ctx_len + mrow;  // last visible position of this lane's row
+        const int limit = a.slot0 + mrow;  // chain: last visible slot of this lane's row
+        // tree rows: the lane's mask row (rows beyond R read row 0 and are dropped by mrow < 0)
+        const uint32_t* mrow_mask = a.tmask ? a.tmask + size_t(mrow < 0 ? 0 : mrow) * a.tmask_words : nullptr;
         int pg = t.pg0 + wave;
         {
             int pid[NBUF];
@@ -1138,6 +1222,15 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
         auto use_two = [&](int pga, const bf16x8 (&ka)[ST], const short4v (&va)[HT], int pgb, const bf16x8 (&kb)[ST],
                            const short4v (&vb)[HT], auto&& scores_done) {
             floatx4 sa = floatx4{0.f, 0.f, 0.f, 0.f}, sb = floatx4{0.f, 0.f, 0.f, 0.f};
+            // Tree rows (draft side: a node sees the context, its ancestors and itself, never its
+            // peers): the 16 visibility bits of each page come from the row's mask word, fetched
+            // here and used after the score instructions.  Pages below the mask's base are context.
+            uint32_t bits_a = 0xffffu, bits_b = 0xffffu;
+            if (mrow_mask) {
+                const int oa = pga * 16 - a.tmask_base, ob = pgb * 16 - a.tmask_base;
+                if (oa >= 0) bits_a = (oa >> 5) < a.tmask_words ? (mrow_mask[oa >> 5] >> (oa & 31)) & 0xffffu : 0u;
+                if (ob >= 0 && pgb < t.pg1) bits_b = (ob >> 5) < a.tmask_words ? (mrow_mask[ob >> 5] >> (ob & 31)) & 0xffffu : 0u;
+            }
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[st], qh[st], sa, 0, 0, 0);
@@ -1150,8 +1243,13 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
             bool oka[4], okb[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                oka[v] = mrow >= 0 && (pga * 16 + kq * 4 + v) <= limit;
-                okb[v] = mrow >= 0 && pgb < t.pg1 && (pgb * 16 + kq * 4 + v) <= limit;
+                if (mrow_mask) {
+                    oka[v] = mrow >= 0 && ((bits_a >> (kq * 4 + v)) & 1u) != 0;
+                    okb[v] = mrow >= 0 && pgb < t.pg1 && ((bits_b >> (kq * 4 + v)) & 1u) != 0;
+                } else {
+                    oka[v] = mrow >= 0 && (pga * 16 + kq * 4 + v) <= limit;
+                    okb[v] = mrow >= 0 && pgb < t.pg1 && (pgb * 16 + kq * 4 + v) <= limit;
+                }
                 if (oka[v]) pmax = fmaxf(pmax, sa[v]);
                 if (okb[v]) pmax = fmaxf(pmax, sb[v]);
             }
@@ -1317,7 +1415,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         const int half = a.h >> 1;
         for (int e = wg * kMegaThreads + tid; e < a.r * half; e += nwg * kMegaThreads) {
             const int m2 = e / half, j = e % half;
-            const double ang = double(a.ctx_len + m2) * pow(double(a.theta), -2.0 * j / a.h);
+            const double ang = double(a.row_pos ? a.row_pos[m2] : a.ctx_len + m2) * pow(double(a.theta), -2.0 * j / a.h);
             st_agent(a.rope + m2 * half + j, float(cos(ang)));
             st_agent(a.rope + kMaxR * half + m2 * half + j, float(sin(ang)));
         }
@@ -1426,14 +1524,95 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
                 const PhasePlan p_lm = stream_phase(a, 4 * a.L, wg, wave);
         EpiArgs ea = {};
         ea.ss_in = a.ss + size_t(2 * a.L) * ss_stride;
+        LmState lm = {{0ull, 0ull}, -1e30f, 0.f};
+        ea.lm = &lm;
         gemm_phase<kNbWide, MT, ME_LM, PK>(a, p_lm, a.xfrag + size_t(2 * a.L) * a.xfrag_stride,
                                           uint32_t(a.xfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
         if (tid < a.r && sm.wg_best[tid] != 0ull)
             __hip_atomic_fetch_max(&a.best[tid], sm.wg_best[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (a.topk > 0) {
+            // this workgroup's share of every row: its sixteen best keys and its (max, sum of exp)
+            constexpr int LPR = kMegaThreads / (16 * MT), RUN = 16 / LPR;
+            const int m = tid / LPR, p = tid % LPR;
+            float mx = lm.m;
+#pragma unroll
+            for (int o = 1; o < LPR; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            float sx = lm.s * __expf(lm.m - mx);
+#pragma unroll
+            for (int o = 1; o < LPR; o <<= 1) sx += __shfl_xor(sx, o);
+            if (m < a.r) {
+                unsigned long long* dst = a.topk_part + (size_t(wg) * kMaxR + m) * 16;
+#pragma unroll
+                for (int u = 0; u < RUN; ++u)
+                    __hip_atomic_store(dst + u * LPR + p, lm.run[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (p == 0) {
+                    st_agent(a.lse_part + (size_t(wg) * kMaxR + m) * 2, mx);
+                    st_agent(a.lse_part + (size_t(wg) * kMaxR + m) * 2 + 1, sx);
+                }
+            }
+        }
     }
     store_wait();
     grid_wait(a, gen, sm, cgen);
 
+    if (a.topk > 0) {
+        // Rows are merged by one workgroup each: thread t holds workgroup t's sorted list of sixteen
+        // keys for the row and its (max, sum) pair; the log-sum-exp folds the pairs, then k rounds of
+        // "largest list head in the workgroup" emit the row's k best tokens with their probabilities.
+        for (int m = wg; m < a.r; m += nwg) {
+            unsigned long long mine[16];
+            float pm = -1e30f, ps = 0.f;
+            if (tid < nwg) {
+                const unsigned long long* src = a.topk_part + (size_t(tid) * kMaxR + m) * 16;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) mine[j] = __hip_atomic_load(src + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pm = ld_agent(a.lse_part + (size_t(tid) * kMaxR + m) * 2);
+                ps = ld_agent(a.lse_part + (size_t(tid) * kMaxR + m) * 2 + 1);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) mine[j] = 0ull;
+            }
+            float* red = sm.wgt;  // [0..3] maxima, [4..7] sums of the four consumer wavefronts
+            float mx = pm;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            if (lane == 0) red[wave] = mx;
+            cbar(sm, cgen);
+            mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+            float sx = ps * __expf(pm - mx);
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) sx += __shfl_xor(sx, o);
+            if (lane == 0) red[4 + wave] = sx;
+            cbar(sm, cgen);
+            const float lse = mx + __logf((red[4] + red[5]) + (red[6] + red[7]));
+            for (int j = 0; j < a.topk; ++j) {
+                unsigned long long best = mine[0];
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const unsigned long long other = __shfl_xor(best, o);
+                    best = other > best ? other : best;
+                }
+                unsigned long long* slot = sm.part_best + (j & 1) * kMegaWaves;
+                if (lane == 0) slot[wave] = best;
+                cbar(sm, cgen);
+                best = slot[0];
+#pragma unroll
+                for (int w2 = 1; w2 < kMegaWaves; ++w2) best = slot[w2] > best ? slot[w2] : best;
+                if (best != 0ull && mine[0] == best) {
+#pragma unroll
+                    for (int i = 0; i < 15; ++i) mine[i] = mine[i + 1];
+                    mine[15] = 0ull;
+                }
+                if (tid == 0) {
+                    const uint32_t kb = uint32_t(best >> 32);
+                    const float logit = __uint_as_float((kb & 0x80000000u) ? (kb & 0x7fffffffu) : ~kb);
+                    a.topk_tok[m * a.topk + j] = best != 0ull ? int(0xffffffffu - uint32_t(best & 0xffffffffull)) : -1;
+                    a.topk_prob[m * a.topk + j] = best != 0ull ? __expf(logit - lse) : 0.f;
+                }
+            }
+            cbar(sm, cgen);
+        }
+    }
     if (wg == 0) {
         if (tid < a.r) {
             const unsigned long long k = __hip_atomic_load(&a.best[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

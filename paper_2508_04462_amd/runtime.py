@@ -99,6 +99,29 @@ class Target:
             res["logits"] = logits.cpu()
         return res
 
+    # -- draft side: one level of cache construction
+    def draft_level(self, ctx_len: int, tokens: Sequence[int], positions: Sequence[int], first_slot: int,
+                    mask_rows: Sequence[Sequence[int]], mask_base: int, k: int, want_logits: bool = False) -> Dict:
+        """Forward the tree nodes `tokens` (at most max_r of them) with card_draft_level; returns the
+        device tensors topk_tokens [n][k] (int32), topk_probs [n][k] (fp32) and, on request, the logits."""
+        n, words = len(tokens), len(mask_rows[0])
+        dev = self.device
+        tok = torch.tensor([int(t) for t in tokens], dtype=torch.int32, device=dev)
+        pos = torch.tensor([int(p) for p in positions], dtype=torch.int32, device=dev)
+        mask = torch.tensor([[int(w) - (1 << 32) if int(w) >= (1 << 31) else int(w) for w in row] for row in mask_rows],
+                            dtype=torch.int32, device=dev)
+        rows = B.CardTreeRows(tok.data_ptr(), pos.data_ptr(), int(first_slot), mask.data_ptr(), words, int(mask_base))
+        tk = torch.full((n, k), -7, dtype=torch.int32, device=dev)
+        tp = torch.zeros((n, k), dtype=torch.float32, device=dev)
+        logits = torch.empty((n, self.cfg.vocab), dtype=torch.float32, device=dev) if want_logits else None
+        _check(B.card_draft_level(self.cfg, self.packed, self.kv(-1), ctx_len, rows, n, k, self.workspace, self._stream(),
+                                  tk, tp, logits), "card_draft_level")
+        torch.cuda.current_stream(dev).synchronize()
+        res = {"topk_tokens": tk, "topk_probs": tp}
+        if want_logits:
+            res["logits"] = logits.cpu()
+        return res
+
     def prefill(self, tokens: Sequence[int], chunk: int = 32) -> int:
         """Build KV[0:n) with verify calls that carry no pending token; returns the arg-max after
         the last context token (the pending prediction g0)."""

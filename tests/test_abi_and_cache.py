@@ -232,3 +232,30 @@ def test_step_begin_argument_errors():
     no_pending = card.CardKV(0x1000, 0x1000, 0x1000, 16, -1)
     assert card.card_step_begin(c.h, cfg, 0x1000, no_pending, 0, 4, 0x1000, 0x1000, None, 0x1000, None, step) == card.CARD_EINVAL
     assert card.card_step_begin(None, cfg, 0x1000, kv, 0, 4, 0x1000, 0x1000, None, 0x1000, None, step) == card.CARD_EINVAL
+
+
+def test_tree_mask_level_matches_the_mask_oracle():
+    """Host mask builder against oracle/cache_oracle.tree_mask (ancestor inheritance + identity,
+    peers invisible) on random trees, with the context bits below the first tree slot."""
+    from oracle.cache_oracle import tree_mask
+
+    rng = np.random.default_rng(3)
+    for ctx_len, widths in [(37, [3, 5, 4, 6]), (16, [1, 2, 9]), (95, [7, 7, 7, 7, 7])]:
+        parents = [[-1] * widths[0]] + [rng.integers(0, widths[l - 1], size=widths[l]).tolist() for l in range(1, len(widths))]
+        ref = tree_mask(parents)
+        offs = np.cumsum([0] + widths)
+        mask_base = ctx_len // 16 * 16
+        tree_base = (ctx_len + 15) // 16 * 16
+        words = (tree_base + int(offs[-1]) - mask_base + 31) // 32
+        prev = None
+        for l, par in enumerate(parents):
+            st, rows = card.card_tree_mask_level(prev, par, tree_base + int(offs[l]), ctx_len, mask_base, words)
+            assert st == card.CARD_OK
+            for i, row in enumerate(rows):
+                bits = {mask_base + 32 * w + b for w in range(words) for b in range(32) if (row[w] >> b) & 1}
+                want = set(range(mask_base, ctx_len)) | {tree_base + int(j) for j in np.flatnonzero(ref[offs[l] + i])}
+                assert bits == want, (l, i)
+            prev = rows
+    assert card.card_tree_mask_level(None, [0], 48, 37, 32, 2)[0] == card.CARD_EINVAL  # a parent without rows
+    assert card.card_tree_mask_level(None, [-1], 30, 37, 32, 2)[0] == card.CARD_ERANGE  # slot inside the context
+    assert card.card_tree_mask_level(None, [-1], 48, 37, 40, 2)[0] == card.CARD_EINVAL  # base not on a page boundary

@@ -415,3 +415,23 @@ def co_kv_prefilled(cfg, w, ctx):
     kv = co.OracleKV.empty(cfg, 64)
     co.prefill(cfg, w, kv, ctx)
     return kv
+
+
+def test_a_stored_full_size_case_is_accepted_in_full_with_every_row_decisive():
+    """The bit-exact accept / correct criterion needs at least one full-size step whose r deciding
+    rows all clear the 0.05 gap (a fully accepted r = 8 step): the stored goldens must hold one."""
+    import glob
+    import json
+    import os
+
+    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    found = []
+    for path in sorted(glob.glob(os.path.join(root, "llama8b_seed*.json"))):
+        with open(path) as f:
+            g = json.load(f)
+        assert g["kv_store"] == "bf16", path
+        w = g.get("window")
+        if w and w["accepted_len"] == g["r"] == 8 and all(gap > 0.05 for gap in w["row_gap"]):
+            assert w["cand"][0] == w["pending"] and w["ctx_len"] == g["ctx"] + len(w["extra_ctx"])
+            found.append(os.path.basename(path))
+    assert found, "no stored full-size step with eight decisive rows"
