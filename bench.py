@@ -291,6 +291,67 @@ def cache_loop(rig, r, p, n_tokens, K=50, width=10):
             "plain_decode_tokens_per_s": None}
 
 
+def concurrent_loop_entries(args, decode_tps, quick):
+    """Draft and target running at the same time on one GPU (two host threads, two streams, the
+    compute units split between the two persistent kernels): the paper's own pairing, a 70B-shaped
+    target (on 192 workgroups) with a 1B-shaped draft (on 64), context 1024, K = 8 nodes per
+    level, top-8 per node, trees four levels deep; the draft's agreement with the target is planted
+    (random-init models never agree).  Accepted tokens/s of the loop beside the target's plain
+    decode rate on the whole GPU: the synthetic form of the paper's speedup over autoregressive
+    decoding."""
+    import card_inputs as ci
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    t_shape = ci.SHAPES["tiny" if quick else "llama70b"]
+    d_shape = ci.ModelShape("tiny-draft", 1, 128, 2, 1, 64, 344, 1024) if quick else ci.SHAPES["llama1b"]
+    ctx_len, n_tok = (128, 24) if quick else (1024, 32)
+    grids = (192, 64)
+    tgt = card.Target(t_shape, ctx_len + 3 * n_tok + 64, grid_wgs=grids[0])
+    load_synthetic_weights(tgt, t_shape, args.seed)
+    dr = card.Target(d_shape, ctx_len + 3 * n_tok + 64 + 16 + 8 * 4 + 64, grid_wgs=grids[1])
+    load_synthetic_weights(dr, d_shape, args.seed + 100)
+    ctx = ci.uniform_tokens(args.seed, "ctx_tokens", 0, ctx_len, t_shape.vocab).tolist()
+    g0 = tgt.prefill(ctx)
+    dr.prefill(ctx)
+    own, pos = [g0], ctx_len
+    t0 = time.perf_counter()
+    for _ in range(3 * n_tok + 8):
+        own.append(tgt.verify(pos, own[-1], [own[-1]])["correction_token"])
+        pos += 1
+    decode_192 = (3 * n_tok + 8) / (time.perf_counter() - t0)
+    out = []
+    n_done = 0
+    for p in ((0.6,) if quick else (0.3, 0.6, 0.9)):
+        # each run continues the text where the previous one stopped
+        loop = card.ConcurrentLoop(tgt, dr, ctx_len + n_done, own[n_done], K=8, k=8, depth=4,
+                                   plant=card.PlantedAgreement(own[n_done:], p, args.seed, t_shape.vocab))
+        loop.d_ctx = ctx_len
+        loop.committed = own[:n_done]
+        loop.d_absorbed = 0
+        e = {"kind": "concurrent_loop", "target": t_shape.name, "draft": d_shape.name, "ctx": ctx_len + n_done,
+             "target_workgroups": grids[0], "draft_workgroups": grids[1], "planted_acceptance": p, "K": 8, "k": 8,
+             "depth": 4, "plain_decode_tokens_per_s_whole_gpu": decode_tps,
+             "plain_decode_tokens_per_s_target_share": decode_192}
+        try:
+            res = loop.run(n_tok)
+            ok = loop.emitted[: n_tok + 1] == own[n_done: n_done + n_tok + 1]
+            e.update(res)
+            e["text_equals_plain_decode"] = ok
+            n_done += res["tokens"]
+        except Exception as ex:  # noqa: BLE001  (a sweep entry must not take the headline down)
+            e["error"] = repr(ex)
+            out.append(e)
+            break
+        out.append(e)
+    tgt = dr = None
+    gc.collect()
+    import torch
+
+    torch.cuda.empty_cache()
+    return out
+
+
 def run_sweep(args, rig8b):
     """Every synthetic configuration besides the headline one.  rig8b: the headline model, reused."""
     import card_inputs as ci
@@ -303,10 +364,14 @@ def run_sweep(args, rig8b):
             continue
         kind = rig8b.set_context(ctx)
         out.append(sweep_point(rig8b, 8, 10 if quick else 20, kind))
+    # the target's plain decode rate on the whole GPU (r = 1 steps), the loop's reference
+    rig8b.set_context(256 if quick else 1024)
+    t0 = time.perf_counter()
+    rig8b.greedy(24)
+    decode_tps = 24 / (time.perf_counter() - t0)
     if quick:
-        rig8b.set_context(256)
-        e = cache_loop(rig8b, 8, 0.6, 16)
-        out.append(e)
+        out.append(cache_loop(rig8b, 8, 0.6, 16))
+        out += concurrent_loop_entries(args, decode_tps, True)
         return out
     rig8b.close()
     # Qwen-7B shape, context 4096: r sweep and the shared-cache loop
@@ -331,7 +396,12 @@ def run_sweep(args, rig8b):
     kind = rig.set_context(shape.ctx)
     for r in (4, 8, 16):
         out.append(sweep_point(rig, r, 8, kind))
+    rig.set_context(1024)
+    t0 = time.perf_counter()
+    rig.greedy(8)
+    decode_tps = 8 / (time.perf_counter() - t0)  # the 70B target's plain decode rate on the whole GPU
     rig.close()
+    out += concurrent_loop_entries(args, decode_tps, False)
     return out
 
 

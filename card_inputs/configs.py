@@ -51,6 +51,7 @@ class ModelShape:
 
 SHAPES = {
     "tiny": ModelShape("tiny", 2, 256, 4, 2, 64, 688, 1024, ctx=128, r=4),
+    "llama1b": ModelShape("llama1b", 16, 2048, 32, 8, 64, 8192, 128256, ctx=1024, r=8),
     "llama8b": ModelShape("llama8b", 32, 4096, 32, 8, 128, 14336, 128256, ctx=1024, r=8),
     "llama70b": ModelShape("llama70b", 80, 8192, 64, 8, 128, 28672, 128256, ctx=2048, r=8),
     "qwen7b": ModelShape("qwen7b", 28, 3584, 28, 4, 128, 18944, 152064, ctx=4096, r=8),

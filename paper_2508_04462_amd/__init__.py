@@ -58,3 +58,4 @@ from .binding import (  # noqa: F401
     card_cache_read_level,
 )
 from .runtime import Target, CandidateCache, make_cfg  # noqa: F401
+from .loop import ConcurrentLoop, PlantedAgreement  # noqa: F401

@@ -175,3 +175,50 @@ def test_step_calls_variable_paths_miss_fallback_and_the_no_correct_variant(flag
     assert hits >= 1 and len(lens) >= 2
     if flags:  # never corrected: the tree the draft wrote stays as written until the next draft
         assert cache.depth() >= 1
+
+
+@pytest.mark.parametrize("p,seed,grids", [(0.7, 11, (128, 64)), (0.95, 42, (192, 64)), (0.0, 27, (64, 32))],
+                         ids=["p0.7", "p0.95", "p0"])
+def test_concurrent_draft_and_target_on_one_gpu_is_lossless(p, seed, grids):
+    """Two models, two host threads, two streams, one GPU: the draft builds cache levels
+    (card_draft_level, card_cache_select, card_cache_write) while the target queries, verifies and
+    corrects; the kernels share the GPU by compute units.  Whatever the interleaving, the emitted
+    text is the target's plain greedy text (checked against the oracle over its decisive prefix
+    and against the target's own token-by-token decode beyond it)."""
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape, n_new = TINY, 40
+    draft_shape = ci.ModelShape("tiny-draft", 1, 128, 2, 1, 64, 344, 1024, ctx=128, r=4)
+    max_ctx = shape.ctx + n_new + 16
+    tgt = card.Target(shape, max_ctx, grid_wgs=grids[0])
+    load_synthetic_weights(tgt, shape, seed)
+    dr = card.Target(draft_shape, shape.ctx + n_new + 16 + 160, grid_wgs=grids[1])
+    load_synthetic_weights(dr, draft_shape, seed + 100)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, shape.ctx, shape.vocab).tolist()
+    w = __import__("oracle.from_inputs", fromlist=["oracle_weights"]).oracle_weights(shape, seed)
+    kv_ref = co.OracleKV.empty(shape, max_ctx)
+    g0_ref = co.prefill(shape, w, kv_ref, ctx)
+    want, gaps = co.greedy_decode_cached(shape, w, kv_ref, shape.ctx, g0_ref, n_new)
+    decisive_upto = next((i for i, g in enumerate(gaps) if g <= GAP), n_new)
+    g0 = tgt.prefill(ctx)
+    # the target's own plain decode: what the loop has to reproduce token for token
+    own, pos = [g0], shape.ctx
+    for _ in range(n_new + 8):
+        own.append(tgt.verify(pos, own[-1], [own[-1]])["correction_token"])
+        pos += 1
+    dr.prefill(ctx)
+    # at these sizes the target is the faster model: for the high planted rate it waits for two levels
+    loop = card.ConcurrentLoop(tgt, dr, shape.ctx, g0, K=8, k=4, depth=3, plant=card.PlantedAgreement(own, p, seed, shape.vocab),
+                               wait_levels=2 if p >= 0.9 else 0)
+    out = loop.run(n_new)
+    assert out["tokens"] >= n_new
+    assert loop.emitted[: n_new + 1] == own[: n_new + 1]
+    if g0 == g0_ref:
+        kk = min(decisive_upto + 1, n_new)
+        assert loop.emitted[:kk] == want[:kk]
+    assert out["steps"] >= 1 and out["draft_restarts"] >= 1
+    if p >= 0.9:
+        assert out["mean_accepted_len"] > 1.5 and out["hit_rate"] > 0.5
+    if p == 0.0:
+        assert out["mean_accepted_len"] == 1.0
