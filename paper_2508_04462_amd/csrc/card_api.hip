@@ -95,7 +95,7 @@ int grid_size(const card_model_cfg* cfg) {
 // workgroup per compute unit, so on an otherwise idle device the dispatcher places all of them.
 // Should other work hold compute units for longer than the kernel's bounded waits, the step ends
 // with accepted_len = -1 instead of hanging.
-template <int MT, int H, bool PK>
+template <int MT, int H, bool PK, bool DR>
 int launch_mega(MegaArgs& a, hipStream_t st) {
     static std::atomic<int> fits[kMaxDevices];  // 0 unknown, 1 yes, -1 no
     int dev = 0;
@@ -103,13 +103,13 @@ int launch_mega(MegaArgs& a, hipStream_t st) {
     int f = fits[dev].load(std::memory_order_relaxed);
     if (f == 0) {
         int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify<MT, H, PK>, kBlockThreads, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify<MT, H, PK, DR>, kBlockThreads, 0) != hipSuccess)
             return CARD_EDEVICE;
         f = per_cu >= 1 ? 1 : -1;
         fits[dev].store(f, std::memory_order_relaxed);
     }
     if (f < 0 || a.nwg > cu_count()) return CARD_EDEVICE;
-    hipLaunchKernelGGL((k_verify<MT, H, PK>), dim3(a.nwg), dim3(kBlockThreads), 0, st, a);
+    hipLaunchKernelGGL((k_verify<MT, H, PK, DR>), dim3(a.nwg), dim3(kBlockThreads), 0, st, a);
     return launch_status();
 }
 
@@ -255,9 +255,14 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.ts_layer = g_ts_layer;
     hipStream_t st = as_stream(stream);
     ProfScope ps(st);
-    if (r <= 8) return h == 128 ? launch_mega<1, 128, true>(a, st) : launch_mega<1, 64, true>(a, st);
-    if (r <= 16) return h == 128 ? launch_mega<1, 128, false>(a, st) : launch_mega<1, 64, false>(a, st);
-    return h == 128 ? launch_mega<2, 128, false>(a, st) : launch_mega<2, 64, false>(a, st);
+    if (tree) {
+        if (r <= 8) return h == 128 ? launch_mega<1, 128, true, true>(a, st) : launch_mega<1, 64, true, true>(a, st);
+        if (r <= 16) return h == 128 ? launch_mega<1, 128, false, true>(a, st) : launch_mega<1, 64, false, true>(a, st);
+        return h == 128 ? launch_mega<2, 128, false, true>(a, st) : launch_mega<2, 64, false, true>(a, st);
+    }
+    if (r <= 8) return h == 128 ? launch_mega<1, 128, true, false>(a, st) : launch_mega<1, 64, true, false>(a, st);
+    if (r <= 16) return h == 128 ? launch_mega<1, 128, false, false>(a, st) : launch_mega<1, 64, false, false>(a, st);
+    return h == 128 ? launch_mega<2, 128, false, false>(a, st) : launch_mega<2, 64, false, false>(a, st);
 }
 
 }  // namespace

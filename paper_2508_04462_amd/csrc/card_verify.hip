@@ -428,7 +428,7 @@ __device__ __forceinline__ float gumbel_noise(uint32_t row_key, uint32_t token) 
     return -logf(-logf(u));
 }
 
-enum MegaEpi { ME_QKV = 0, ME_RESID = 1, ME_SWIGLU = 2, ME_LM = 3 };
+enum MegaEpi { ME_QKV = 0, ME_RESID = 1, ME_SWIGLU = 2, ME_LM = 3, ME_LM_TOPK = 4 };
 
 // Running state of one thread across the batches of the vocabulary phase when the phase keeps a
 // per-row top-k and a log-sum-exp (draft side) instead of the arg-max.
@@ -741,7 +741,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                 const int f0 = (tile0 + i * a.nwg) * 8;
                 st_dev_frag8(ea.actfrag, frag_index(f0, m, rp), av);
             }
-        } else if constexpr (EPI == ME_LM) {
+        } else if constexpr (EPI == ME_LM || EPI == ME_LM_TOPK) {
             if (a.logits) {
                 for (int e = tid; e < NBS * 16 * r; e += kMegaThreads) {
                     const int nl = e % (NBS * 16), m = e / (NBS * 16);
@@ -750,7 +750,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                     if (i < nvalid_s && n < a.V) a.logits[size_t(m) * a.V + n] = sm.tile[nl * COLS + m] * sm.row_scale[m];
                 }
             }
-            if (a.topk > 0) {
+            if constexpr (EPI == ME_LM_TOPK) {
                 // Draft side (Cache Construction, eqs. (1)-(2)): per row the k most probable tokens and
                 // the log-sum-exp that turns their logits into probabilities, without storing the
                 // row.  The lanes of a row are consecutive (16 of them with one row tile, 8 with
@@ -1167,7 +1167,7 @@ __device__ __forceinline__ void attn_page_ids(const MegaArgs& a, int wave, int w
     }
 }
 
-template <int H>
+template <int H, bool TREE>
 __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSmem& sm, int wave, int lane, int wg,
                                            AttnBufs<H>& bf, const int (&pid0)[8], bool (&loaded)[8], uint32_t& cgen) {
     constexpr int ST = H / 32, HT = H / 16, PART = 16 * (H + 2), NBUF = AttnBufs<H>::N;
@@ -1185,7 +1185,7 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
         const int mrow = row_ok ? rho / a.G : -1;
         const int limit = a.slot0 + mrow;  // chain: last visible slot of this lane's row
         // tree rows: the lane's mask row (rows beyond R read row 0 and are dropped by mrow < 0)
-        const uint32_t* mrow_mask = a.tmask ? a.tmask + size_t(mrow < 0 ? 0 : mrow) * a.tmask_words : nullptr;
+        const uint32_t* mrow_mask = TREE ? a.tmask + size_t(mrow < 0 ? 0 : mrow) * a.tmask_words : nullptr;
         int pg = t.pg0 + wave;
         {
             int pid[NBUF];
@@ -1226,7 +1226,7 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
             // peers): the 16 visibility bits of each page come from the row's mask word, fetched
             // here and used after the score instructions.  Pages below the mask's base are context.
             uint32_t bits_a = 0xffffu, bits_b = 0xffffu;
-            if (mrow_mask) {
+            if constexpr (TREE) {
                 const int oa = pga * 16 - a.tmask_base, ob = pgb * 16 - a.tmask_base;
                 if (oa >= 0) bits_a = (oa >> 5) < a.tmask_words ? (mrow_mask[oa >> 5] >> (oa & 31)) & 0xffffu : 0u;
                 if (ob >= 0 && pgb < t.pg1) bits_b = (ob >> 5) < a.tmask_words ? (mrow_mask[ob >> 5] >> (ob & 31)) & 0xffffu : 0u;
@@ -1243,7 +1243,7 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
             bool oka[4], okb[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                if (mrow_mask) {
+                if constexpr (TREE) {
                     oka[v] = mrow >= 0 && ((bits_a >> (kq * 4 + v)) & 1u) != 0;
                     okb[v] = mrow >= 0 && pgb < t.pg1 && ((bits_b >> (kq * 4 + v)) & 1u) != 0;
                 } else {
@@ -1347,7 +1347,8 @@ __device__ __forceinline__ void attn_phase(const MegaArgs& a, int layer, MegaSme
     }
 }
 // ---- the kernel ----------------------------------------------------------------------------------
-template <int MT, int H, bool PK>
+// DR: draft-side call (tree rows with a visibility mask, per-row top-k in the vocabulary phase)
+template <int MT, int H, bool PK, bool DR>
 __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_verify(MegaArgs a) {
     __shared__ MegaSmem sm;
     const int tid = threadIdx.x;
@@ -1469,7 +1470,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         CARD_TS(12)
         grid_wait(a, gen, sm, cgen);
         CARD_TS(2)
-        attn_phase<H>(a, l, sm, wave, lane, wg, bf, pid0, loaded, cgen);
+        attn_phase<H, DR>(a, l, sm, wave, lane, wg, bf, pid0, loaded, cgen);
         CARD_TS(3)
         store_wait();
         grid_wait(a, gen, sm, cgen);
@@ -1526,11 +1527,11 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         ea.ss_in = a.ss + size_t(2 * a.L) * ss_stride;
         LmState lm = {{0ull, 0ull}, -1e30f, 0.f};
         ea.lm = &lm;
-        gemm_phase<kNbWide, MT, ME_LM, PK>(a, p_lm, a.xfrag + size_t(2 * a.L) * a.xfrag_stride,
+        gemm_phase<kNbWide, MT, DR ? ME_LM_TOPK : ME_LM, PK>(a, p_lm, a.xfrag + size_t(2 * a.L) * a.xfrag_stride,
                                           uint32_t(a.xfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
         if (tid < a.r && sm.wg_best[tid] != 0ull)
             __hip_atomic_fetch_max(&a.best[tid], sm.wg_best[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (a.topk > 0) {
+        if constexpr (DR) {
             // this workgroup's share of every row: its sixteen best keys and its (max, sum of exp)
             constexpr int LPR = kMegaThreads / (16 * MT), RUN = 16 / LPR;
             const int m = tid / LPR, p = tid % LPR;
@@ -1555,7 +1556,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
     store_wait();
     grid_wait(a, gen, sm, cgen);
 
-    if (a.topk > 0) {
+    if constexpr (DR) {
         // Rows are merged by one workgroup each: thread t holds workgroup t's sorted list of sixteen
         // keys for the row and its (max, sum) pair; the log-sum-exp folds the pairs, then k rounds of
         // "largest list head in the workgroup" emit the row's k best tokens with their probabilities.
