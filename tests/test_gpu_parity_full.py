@@ -110,7 +110,9 @@ def test_tiny_against_stored_oracle_values():
     assert g["kv_store"] == "bf16" and "window" in g
 
 
-FULL = sorted(f for f in os.listdir(GOLDEN) if f.startswith("llama8b_seed") and f.endswith(".json"))
+FULL = sorted(f for f in os.listdir(GOLDEN) if f.startswith("llama8b_seed") and f.endswith(".json") and "_ctx" not in f)
+# full-depth cases at other shapes / context lengths (file name: <shape>_seed<seed>_ctx<N>.json)
+OTHER = sorted(f for f in os.listdir(GOLDEN) if "_ctx" in f and f.endswith(".json"))
 
 
 @pytest.mark.parametrize("golden_name", FULL)
@@ -119,4 +121,14 @@ def test_full_size_workload_against_stored_oracle_values(golden_name):
     per compute unit; planted prefixes j = 0, 4, 8; one case per stored seed."""
     g = _run(golden_name, LOGIT_TOL_FULL)
     assert g["shape"] == "llama8b" and g["ctx"] == 1024 and g["r"] == 8 and g["kv_store"] == "bf16"
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("golden_name", OTHER)
+def test_full_depth_at_other_shapes_and_contexts(golden_name):
+    """Full depth where the host oracle can reach it: the Qwen-7B-shaped model (28 layers) and the
+    8B shape at a context long enough for many cuts of the page list and in-loop page refills at
+    the real widths.  Same bars as the headline workload."""
+    g = _run(golden_name, LOGIT_TOL_FULL)
+    assert g["kv_store"] == "bf16" and ci.SHAPES[g["shape"]].n_layers >= 28
     torch.cuda.synchronize()
