@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", choices=["full", "quick", "none"], default="full",
                     help="full: every synthetic configuration; quick: one point per kind on the headline shape; none")
+    ap.add_argument("--draft-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: three cache levels of K = 100 nodes on the 1B-shaped draft, no timing")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a 1 GiB device copy (calibration) and 5 verify steps, no timing")
     return ap.parse_args()
@@ -352,6 +354,84 @@ def concurrent_loop_entries(args, decode_tps, quick):
     return out
 
 
+def draft_level_entry(args, quick, probe_levels=0):
+    """The draft side of cache construction (Cache Construction, eqs. (1)-(9)) as one sweep entry: a
+    1B-shaped draft on the whole GPU builds cache levels of K = 100 nodes, top-8 per node, below a
+    root behind 1024 tokens of context.  A level is forwarded in ceil(K / 32) calls of the
+    draft-mode kernel (tree positions, slots, ancestor mask; per-row top-k and log-sum-exp fused
+    into the vocabulary phase), then card_cache_select takes the global top-K of the K * k path
+    scores.  Timed: level 2 onwards (parents spread over the level above), host synchronisation
+    after every call included.  probe_levels > 0: no timing, that many levels (for counter runs)."""
+    import numpy as np
+    import torch
+
+    import card_inputs as ci
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape = ci.ModelShape("tiny-draft", 1, 128, 2, 1, 64, 344, 1024) if quick else ci.SHAPES["llama1b"]
+    ctx_len, K, k = (64, 40, 4) if quick else (1024, 100, 8)
+    n_levels = probe_levels if probe_levels else (2 if quick else 4)
+    dr = card.Target(shape, ctx_len + 16 + K * (n_levels + 1) + 64, max_r=32)
+    load_synthetic_weights(dr, shape, args.seed + 100)
+    dev = dr.device
+    root = dr.prefill(ci.uniform_tokens(args.seed, "ctx_tokens", 0, ctx_len, shape.vocab).tolist())
+    mask_base = ctx_len // 16 * 16
+    words = (ctx_len + 1 + K * (n_levels + 1) - mask_base + 31) // 32
+    assert words <= 32
+
+    def forward(tokens, parents, prev_rows, first, position, sigma):
+        """One level: mask rows, the forward calls, the selection of the next level."""
+        st, rows = card.card_tree_mask_level(prev_rows, parents, first, ctx_len, mask_base, words)
+        assert st == card.CARD_OK
+        n = len(tokens)
+        tk = torch.empty((n, k), dtype=torch.int32, device=dev)
+        tp = torch.empty((n, k), dtype=torch.float32, device=dev)
+        calls = 0
+        for c0 in range(0, n, 32):
+            c1 = min(n, c0 + 32)
+            res = dr.draft_level(ctx_len, tokens[c0:c1], [position] * (c1 - c0), first + c0, rows[c0:c1], mask_base, k)
+            tk[c0:c1], tp[c0:c1] = res["topk_tokens"], res["topk_probs"]
+            calls += 1
+        ot = torch.empty(K, dtype=torch.int32, device=dev)
+        os_ = torch.empty(K, dtype=torch.float32, device=dev)
+        op = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = card.card_cache_select(sigma, tk, tp, n, k, K, ot, os_, op, torch.cuda.current_stream(dev).cuda_stream)
+        if cnt < 0:
+            raise card.CardError(cnt, "card_cache_select")
+        torch.cuda.synchronize()
+        return rows, ot[:cnt].tolist(), op[:cnt].tolist(), os_[:cnt].clone(), calls
+
+    # level 0: the root alone; its children are level 1
+    rows, toks, pars, sigma, _ = forward([root], [-1], None, ctx_len, ctx_len, torch.ones(1, dtype=torch.float32, device=dev))
+    first, times, calls = ctx_len + 1, [], 0
+    for l in range(1, n_levels + 1):
+        t0 = time.perf_counter()
+        rows, ntoks, npars, nsigma, c = forward(toks, pars, rows, first, ctx_len + l, sigma)
+        if l >= 2 or n_levels == 1:
+            times.append((time.perf_counter() - t0) * 1e3)
+            calls = c
+        first += len(toks)
+        n_nodes = len(toks)
+        toks, pars, sigma = ntoks, npars, nsigma
+    dr = None
+    gc.collect()
+    torch.cuda.empty_cache()
+    if probe_levels:
+        return {"draft_probe": True, "levels": n_levels, "K": K, "k": k}
+    ms = float(np.median(times))
+    params = shape.streamed_weight_bytes() // 2
+    rows_issued = 32 * (n_nodes // 32) + (0 if n_nodes % 32 == 0 else (8 if n_nodes % 32 <= 8 else 16 if n_nodes % 32 <= 16 else 32))
+    return {"kind": "draft_level", "draft": shape.name, "ctx": ctx_len, "K": n_nodes, "k": k, "calls_per_level": calls,
+            "ms_per_level": ms, "ms_per_call": ms / calls, "nodes_per_s": n_nodes / (ms * 1e-3),
+            "hbm_frac": calls * (shape.streamed_weight_bytes() + shape.kv_bytes(ctx_len)) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            # matrix-pipe work issued: two instructions (high and low activation halves) per weight
+            # fragment and 16-row tile, padded rows included, against the dense bf16 peak
+            "mfma_tflops_issued": 2 * 2 * rows_issued * params / (ms * 1e-3) / 1e12,
+            "mfma_frac_of_bf16_peak": 2 * 2 * rows_issued * params / (ms * 1e-3) / 2.5e15,
+            "model_tflops": 2 * n_nodes * params / (ms * 1e-3) / 1e12}
+
+
 def run_sweep(args, rig8b):
     """Every synthetic configuration besides the headline one.  rig8b: the headline model, reused."""
     import card_inputs as ci
@@ -372,6 +452,7 @@ def run_sweep(args, rig8b):
     if quick:
         out.append(cache_loop(rig8b, 8, 0.6, 16))
         out += concurrent_loop_entries(args, decode_tps, True)
+        out.append(draft_level_entry(args, True))
         return out
     rig8b.close()
     # Qwen-7B shape, context 4096: r sweep and the shared-cache loop
@@ -402,6 +483,7 @@ def run_sweep(args, rig8b):
     decode_tps = 8 / (time.perf_counter() - t0)  # the 70B target's plain decode rate on the whole GPU
     rig.close()
     out += concurrent_loop_entries(args, decode_tps, False)
+    out.append(draft_level_entry(args, False))
     return out
 
 
@@ -421,6 +503,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.draft_probe:
+        print(json.dumps(draft_level_entry(args, False, probe_levels=3)))
+        return
     sweep_ctx = 0 if args.sweep == "none" or args.shape != "llama8b" else (512 if args.sweep == "quick" else 32768)
     rig = Rig(shape, args.seed, max(ctx, sweep_ctx))
     rig.set_context(ctx)

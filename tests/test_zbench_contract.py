@@ -44,11 +44,13 @@ def test_short_run_prints_one_json_line_with_the_contract_fields(monkeypatch, ca
     assert rf["traffic"] is None or rf["traffic"] >= 0.9 * d["algorithmic_bytes_per_step"]
     # the other synthetic configurations ride in the same line
     sw = d["sweep"]
-    pts = [e for e in sw if e.get("kind") not in ("cache_loop", "concurrent_loop")]
+    pts = [e for e in sw if e.get("kind") not in ("cache_loop", "concurrent_loop", "draft_level")]
     assert pts and all(e["ms_per_step"] > 0 and 0.1 < e["hbm_frac"] < 1.0 and e["verified_tokens_per_s"] > 0 for e in pts)
     conc = [e for e in sw if e.get("kind") == "concurrent_loop"]
     assert conc and all("error" in e or (e["text_equals_plain_decode"] and e["accepted_tokens_per_s"] > 0) for e in conc)
     pts = [e for e in pts if e.get("kind") != "concurrent_loop"]
+    dl = [e for e in sw if e.get("kind") == "draft_level"]
+    assert len(dl) == 1 and dl[0]["ms_per_level"] > 0 and dl[0]["calls_per_level"] == (dl[0]["K"] + 31) // 32
     loops = [e for e in sw if e.get("kind") == "cache_loop"]
     assert loops and all("error" in e or (e["accepted_tokens_per_s"] > 0 and 1.0 <= e["mean_accepted_len"] <= e["r"])
                          for e in loops)
