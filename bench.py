@@ -297,7 +297,8 @@ def concurrent_loop_entries(args, decode_tps, quick):
     """Draft and target running at the same time on one GPU (two host threads, two streams, the
     compute units split between the two persistent kernels): the paper's own pairing, a 70B-shaped
     target (on 192 workgroups) with a 1B-shaped draft (on 64), context 1024, K = 8 nodes per
-    level, top-8 per node, trees four levels deep; the draft's agreement with the target is planted
+    level, top-8 per node, the draft up to twelve levels ahead of the token verified last, the
+    target verifying up to eight tokens per step; the draft's agreement with the target is planted
     (random-init models never agree).  Accepted tokens/s of the loop beside the target's plain
     decode rate on the whole GPU: the synthetic form of the paper's speedup over autoregressive
     decoding."""
@@ -307,11 +308,12 @@ def concurrent_loop_entries(args, decode_tps, quick):
 
     t_shape = ci.SHAPES["tiny" if quick else "llama70b"]
     d_shape = ci.ModelShape("tiny-draft", 1, 128, 2, 1, 64, 344, 1024) if quick else ci.SHAPES["llama1b"]
-    ctx_len, n_tok = (128, 24) if quick else (1024, 32)
+    ctx_len, n_tok = (128, 24) if quick else (1024, 64)
     grids = (192, 64)
+    depth, r_max = (3, 4) if quick else (12, 8)
     tgt = card.Target(t_shape, ctx_len + 3 * n_tok + 64, grid_wgs=grids[0])
     load_synthetic_weights(tgt, t_shape, args.seed)
-    dr = card.Target(d_shape, ctx_len + 3 * n_tok + 64 + 16 + 8 * 4 + 64, grid_wgs=grids[1])
+    dr = card.Target(d_shape, ctx_len + 3 * n_tok + (256 if quick else 1024) + 64, grid_wgs=grids[1])
     load_synthetic_weights(dr, d_shape, args.seed + 100)
     ctx = ci.uniform_tokens(args.seed, "ctx_tokens", 0, ctx_len, t_shape.vocab).tolist()
     g0 = tgt.prefill(ctx)
@@ -326,14 +328,14 @@ def concurrent_loop_entries(args, decode_tps, quick):
     n_done = 0
     for p in ((0.6,) if quick else (0.3, 0.6, 0.9)):
         # each run continues the text where the previous one stopped
-        loop = card.ConcurrentLoop(tgt, dr, ctx_len + n_done, own[n_done], K=8, k=8, depth=4,
+        loop = card.ConcurrentLoop(tgt, dr, ctx_len + n_done, own[n_done], K=8, k=8, depth=depth, r_max=r_max,
                                    plant=card.PlantedAgreement(own[n_done:], p, args.seed, t_shape.vocab))
         loop.d_ctx = ctx_len
         loop.committed = own[:n_done]
         loop.d_absorbed = 0
         e = {"kind": "concurrent_loop", "target": t_shape.name, "draft": d_shape.name, "ctx": ctx_len + n_done,
              "target_workgroups": grids[0], "draft_workgroups": grids[1], "planted_acceptance": p, "K": 8, "k": 8,
-             "depth": 4, "plain_decode_tokens_per_s_whole_gpu": decode_tps,
+             "depth": depth, "r_max": r_max, "plain_decode_tokens_per_s_whole_gpu": decode_tps,
              "plain_decode_tokens_per_s_target_share": decode_192}
         try:
             res = loop.run(n_tok)

@@ -259,3 +259,58 @@ def test_tree_mask_level_matches_the_mask_oracle():
     assert card.card_tree_mask_level(None, [0], 48, 37, 32, 2)[0] == card.CARD_EINVAL  # a parent without rows
     assert card.card_tree_mask_level(None, [-1], 30, 37, 32, 2)[0] == card.CARD_ERANGE  # slot inside the context
     assert card.card_tree_mask_level(None, [-1], 48, 37, 40, 2)[0] == card.CARD_EINVAL  # base not on a page boundary
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_the_draft_loop_rerooting_of_its_own_tree_record_follows_the_cache(seed):
+    """The concurrent loop's draft keeps a record of the tree beside the cache (slots and mask rows
+    of the nodes it has forwarded) and re-roots it itself after every correction: same lookup rule,
+    same surviving nodes in the same order, same parent indices as card_cache_correct."""
+    from paper_2508_04462_amd.loop import ConcurrentLoop, _Level
+
+    rng = np.random.default_rng(100 + seed)
+    K, depth, vocab = 6, 5, 5
+    loop = object.__new__(ConcurrentLoop)
+    loop.cache = card.CandidateCache(K, depth)
+    loop.mirror, loop.base_row, loop.pos0 = [], None, 40
+    loop.stats = {"rerooted": 0}
+    for _ in range(8):
+        # (re)fill below what is left, as the draft would; forwarded nodes get a slot and a row tag
+        for l in range(len(loop.mirror), depth):
+            n_prev = len(loop.mirror[l - 1].tok) if l else 0
+            n = int(rng.integers(1, K + 1))
+            t = rng.integers(0, vocab, size=n).tolist()
+            p = [-1] * n if l == 0 else rng.integers(0, n_prev, size=n).tolist()
+            s = (rng.integers(1, 64, size=n) / 64.0).tolist()
+            assert loop.cache.write(l, t, p, s) == card.CARD_OK
+            lv = _Level(t, p, s)
+            lv.slot = [1000 * l + i for i in range(n)]
+            lv.row = [[l, i] for i in range(n)]
+            loop.mirror.append(lv)
+        assert loop._mirror_matches_cache()
+        tok0 = loop.mirror[0].tok[int(rng.integers(len(loop.mirror[0].tok)))]
+        hit, chain, _ = loop.cache.query(tok0, int(rng.integers(1, depth + 1)))
+        assert hit
+        if rng.random() < 0.25:
+            chain = chain + [vocab + 3]  # leaves the tree: both sides end up empty
+        pos_before, last = loop.pos0, None
+        # the record's row of the node verified last is what the new level 0 inherits
+        node = -1
+        for d, t in enumerate(chain):
+            if d >= len(loop.mirror):
+                node = -1
+                break
+            cands = [i for i, tt in enumerate(loop.mirror[d].tok) if tt == t and (d == 0 or loop.mirror[d].par[i] == node)]
+            if not cands:
+                node = -1
+                break
+            node = max(cands, key=lambda i: (loop.mirror[d].score[i], -i))
+            last = loop.mirror[d].row[node]
+        loop.cache.correct(chain)
+        loop._mirror_correct(chain)
+        assert loop._mirror_matches_cache()
+        if loop.mirror:
+            assert node >= 0 and loop.base_row == last and loop.pos0 == pos_before + len(chain)
+            # slots and rows travelled with their nodes
+            for lv in loop.mirror:
+                assert all(r[1] == s % 1000 for r, s in zip(lv.row, lv.slot))

@@ -209,8 +209,10 @@ def test_concurrent_draft_and_target_on_one_gpu_is_lossless(p, seed, grids):
         pos += 1
     dr.prefill(ctx)
     # at these sizes the target is the faster model: for the high planted rate it waits for two levels
-    loop = card.ConcurrentLoop(tgt, dr, shape.ctx, g0, K=8, k=4, depth=3, plant=card.PlantedAgreement(own, p, seed, shape.vocab),
-                               wait_levels=2 if p >= 0.9 else 0)
+    # (the draft may run six levels ahead of a target that verifies three tokens per step, so that part of
+    # the tree outlives a correction)
+    loop = card.ConcurrentLoop(tgt, dr, shape.ctx, g0, K=8, k=4, depth=6 if p >= 0.9 else 3, r_max=3 if p >= 0.9 else None,
+                               plant=card.PlantedAgreement(own, p, seed, shape.vocab), wait_levels=2 if p >= 0.9 else 0)
     out = loop.run(n_new)
     assert out["tokens"] >= n_new
     assert loop.emitted[: n_new + 1] == own[: n_new + 1]
@@ -220,5 +222,7 @@ def test_concurrent_draft_and_target_on_one_gpu_is_lossless(p, seed, grids):
     assert out["steps"] >= 1 and out["draft_restarts"] >= 1
     if p >= 0.9:
         assert out["mean_accepted_len"] > 1.5 and out["hit_rate"] > 0.5
+        # the draft went on below the verified tokens instead of starting a new tree after every step
+        assert out["trees_kept_across_corrections"] >= 1
     if p == 0.0:
         assert out["mean_accepted_len"] == 1.0
