@@ -51,8 +51,9 @@ def test_missing_library_fails_loudly_at_first_use(tmp_path):
     """No fallback: with no libcard.so beside the binding the first entry point raises."""
     pkg = tmp_path / "paper_2508_04462_amd"
     pkg.mkdir()
-    for f in ("__init__.py", "binding.py", "runtime.py", "synthetic.py", "build.py"):
-        shutil.copyfile(os.path.join(ROOT, "paper_2508_04462_amd", f), pkg / f)
+    for f in os.listdir(os.path.join(ROOT, "paper_2508_04462_amd")):
+        if f.endswith(".py"):
+            shutil.copyfile(os.path.join(ROOT, "paper_2508_04462_amd", f), pkg / f)
     shutil.copytree(os.path.join(ROOT, "card_inputs"), tmp_path / "card_inputs")
     env = {k: v for k, v in os.environ.items() if k != "PYTHONPATH"}
     code = ("import paper_2508_04462_amd as c\n"
