@@ -7,6 +7,8 @@ Usage:
       (full-size shapes: about an hour on 8 cores, 30 GB of host memory)
   python tests/golden/make_golden.py tiny-planted
       (seconds)
+  python tests/golden/make_golden.py draft llama1b 1
+      (a few minutes)
 
 Per-shape output tests/golden/<shape>_seed<seed>[_ctx<N>].json: the greedy stream g0..g_r of the
 oracle after a context of N uniform tokens with each step's top-1/top-2 gap, and for the planted
@@ -16,6 +18,12 @@ consecutive rows whose gap exceeds 0.05: a verify step placed there (context = t
 followed by the stream up to that point, candidates = the next r greedy tokens) is accepted in
 full and every row that decides it is decisive, so the HIP path has to reproduce accepted_len = r
 and the correction token bit-exactly.  That case is stored under "window".
+
+draft writes tests/golden/<shape>_seed<seed>_draft.json: the draft-side tree forward (Cache
+Construction, eq. (1)-(2); Mask Construction for Draft Model) at full depth.  Behind a context of
+N uniform tokens sits a tree of three levels (the root, 40 nodes, 24 nodes; seeded random tokens
+and parents); per node the oracle's k + 1 largest logits with their tokens, the log-sum-exp of the
+row, its largest |logit| and a sample of logits.
 
 tiny-planted writes tests/golden/tiny_planted_kept.json: for the small configuration, seeds
 1..20 and every planted prefix length j, whether all deciding rows are decisive in the oracle,
@@ -76,9 +84,59 @@ def tiny_planted():
     print("wrote", path, out["n_kept"], "of", 20 * (shape.r + 1))
 
 
+def draft_golden(name, seed, k=8):
+    from oracle.cache_oracle import tree_mask
+
+    shape = ci.SHAPES[name]
+    n_ctx = shape.ctx
+    dt = np.float32 if shape.d_model >= 2048 else np.float64
+    t0 = time.time()
+    w = oracle_weights(shape, seed, dtype=dt)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, n_ctx, shape.vocab).tolist()
+    widths = [1, 40, 24]
+    tree_base = (n_ctx + 15) // 16 * 16
+    kv = co.OracleKV.empty(shape, tree_base + sum(widths) + 8, dt)
+    g0 = co.prefill(shape, w, kv, ctx, dt, chunk=128)
+    print(f"prefill done {time.time() - t0:.0f}s g0={g0}", flush=True)
+    rng = np.random.default_rng(seed)
+    levels, prev = [], 0
+    for l, n in enumerate(widths):
+        toks = [int(g0)] if l == 0 else rng.integers(0, shape.vocab, size=n).tolist()
+        parents = [-1] * n if l == 0 else rng.integers(0, prev, size=n).tolist()
+        levels.append((toks, parents))
+        prev = n
+    mask = tree_mask([p for _, p in levels])
+    offs = np.cumsum([0] + widths)
+    sample_idx = sorted(set(np.random.default_rng(1234).integers(0, shape.vocab, size=48).tolist()))
+    out_levels = []
+    for l, (toks, parents) in enumerate(levels):
+        n = len(toks)
+        first = tree_base + int(offs[l])
+        visible = [list(range(n_ctx)) + [tree_base + int(j) for j in np.flatnonzero(mask[offs[l] + i])] for i in range(n)]
+        logits = co.forward_tree_rows(shape, w, kv, toks, [n_ctx + l] * n, [first + i for i in range(n)], visible, dt)
+        rows = []
+        for row in logits.astype(np.float64):
+            order = sorted(range(row.shape[0]), key=lambda t: (-row[t], t))[: k + 1]
+            lse = float(np.log(np.exp(row - row.max()).sum()) + row.max())
+            rows.append({"top": [int(t) for t in order], "top_logits": [float(row[t]) for t in order], "lse": lse,
+                         "absmax": float(np.abs(row).max()), "logit_sample": [float(row[i]) for i in sample_idx]})
+        out_levels.append({"tokens": [int(t) for t in toks], "parents": [int(q) for q in parents], "first_slot": first,
+                           "position": n_ctx + l, "rows": rows})
+        print(f"level {l}: {n} rows {time.time() - t0:.0f}s", flush=True)
+    out = {"shape": name, "seed": seed, "ctx": n_ctx, "k": k, "tree_base": tree_base, "oracle_dtype": str(np.dtype(dt)),
+           "kv_store": kv.store, "g0": int(g0), "sample_idx": sample_idx, "levels": out_levels}
+    path = os.path.join(GOLDEN, f"{name}_seed{seed}_draft.json")
+    with open(path, "w") as f:
+        json.dump(out, f)
+    print("wrote", path, f"{time.time() - t0:.0f}s", flush=True)
+
+
 def main():
     if len(sys.argv) > 1 and sys.argv[1] == "tiny-planted":
         tiny_planted()
+        return
+    if len(sys.argv) > 3 and sys.argv[1] == "draft":
+        draft_golden(sys.argv[2], int(sys.argv[3]))
         return
     ap = argparse.ArgumentParser()
     ap.add_argument("shape")

@@ -132,3 +132,69 @@ def test_full_depth_at_other_shapes_and_contexts(golden_name):
     g = _run(golden_name, LOGIT_TOL_FULL)
     assert g["kv_store"] == "bf16" and ci.SHAPES[g["shape"]].n_layers >= 28
     torch.cuda.synchronize()
+
+
+DRAFT = sorted(f for f in os.listdir(GOLDEN) if f.endswith("_draft.json"))
+
+
+@pytest.mark.parametrize("golden_name", DRAFT)
+def test_draft_tree_forward_at_full_depth(golden_name):
+    """card_draft_level on the 1B-shaped draft (16 layers, context 1024) against stored oracle values:
+    a tree of 1 + 40 + 24 nodes, the 40-node level in two calls.  Sampled logits within the bar of
+    the verify step; the returned top-k set equals the oracle's where the k-th and (k+1)-th oracle
+    logits are more than 0.05 apart, rank j holds the oracle's token while every gap down to rank j
+    is that large; every returned probability is the softmax value of that token in the path's own logit
+    row (5e-3 in the logarithm), whose log-sum-exp lies within the logit bar of the oracle's."""
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    with open(os.path.join(GOLDEN, golden_name)) as f:
+        g = json.load(f)
+    shape, seed, ctx_len, k = ci.SHAPES[g["shape"]], g["seed"], g["ctx"], g["k"]
+    assert g["kv_store"] == "bf16"
+    n_nodes = sum(len(lv["tokens"]) for lv in g["levels"])
+    max_ctx = (g["tree_base"] + n_nodes + 8 + 15) // 16 * 16
+    tgt = card.Target(shape, max_ctx, max_r=32, page_order=shuffled_pages(max_ctx // 16, seed))
+    load_synthetic_weights(tgt, shape, seed)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, ctx_len, shape.vocab).tolist()
+    g0 = tgt.prefill(ctx)
+    idx = g["sample_idx"]
+    mask_base = ctx_len // 16 * 16
+    words = (g["tree_base"] + n_nodes - mask_base + 31) // 32
+    prev_rows, worst, sets, orders = None, 0.0, 0, 0
+    for l, lv in enumerate(g["levels"]):
+        toks, parents, first = lv["tokens"], lv["parents"], lv["first_slot"]
+        st, rows = card.card_tree_mask_level(prev_rows, parents, first, ctx_len, mask_base, words)
+        assert st == card.CARD_OK
+        for c0 in range(0, len(toks), 32):
+            c1 = min(len(toks), c0 + 32)
+            res = tgt.draft_level(ctx_len, toks[c0:c1], [lv["position"]] * (c1 - c0), first + c0, rows[c0:c1], mask_base, k,
+                                  want_logits=True)
+            tk, tp = res["topk_tokens"].cpu().numpy(), res["topk_probs"].cpu().double().numpy()
+            for i in range(c0, c1):
+                ref = lv["rows"][i]
+                got = res["logits"][i - c0].double().numpy()
+                err = float(np.abs(got[idx] - np.array(ref["logit_sample"])).max() / ref["absmax"])
+                worst = max(worst, err)
+                assert err <= LOGIT_TOL_FULL, (l, i, err)
+                top, tl = ref["top"], ref["top_logits"]
+                mine = tk[i - c0].tolist()
+                assert len(set(mine)) == k and all(tp[i - c0][j] >= tp[i - c0][j + 1] for j in range(k - 1))
+                # probabilities: the softmax of the path's own logit row (fused online log-sum-exp against the
+                # plain one in fp64), and that log-sum-exp within the logit bar of the oracle's
+                lse = float(np.log(np.exp(got - got.max()).sum()) + got.max())
+                assert abs(lse - ref["lse"]) <= LOGIT_TOL_FULL * ref["absmax"], (l, i)
+                for j, t in enumerate(mine):
+                    assert abs(np.log(tp[i - c0][j]) - (got[t] - lse)) <= 5e-3, (l, i, j)
+                if tl[k - 1] - tl[k] > GAP:
+                    assert set(mine) == set(top[:k]), (l, i)
+                    sets += 1
+                for j in range(k):  # rank j is fixed while every gap down to it is decisive
+                    if tl[j] - tl[j + 1] <= GAP:
+                        break
+                    assert mine[j] == top[j], (l, i, j)
+                    orders += 1
+        prev_rows = rows
+    print(f"[{golden_name}] worst sampled logit error {worst:.2e} of the row maximum; {sets} rows with a decisive top-{k} set, "
+          f"{orders} decisive ranks; g0 {'equal' if g0 == g['g0'] else 'differs (near tie)'}")
+    assert sets >= 8 and orders >= 40
