@@ -115,15 +115,20 @@ class ConcurrentLoop:
     them as the draft made them."""
 
     def __init__(self, target: Target, draft: Target, ctx_len: int, pending: int, K: int = 32, k: int = 8, depth: int = 4,
-                 plant: Optional[Callable] = None, wait_levels: int = 0, wait_ms: float = 20.0, r_max: Optional[int] = None):
+                 plant: Optional[Callable] = None, wait_levels: int = 0, wait_ms: float = 20.0, r_max: Optional[int] = None,
+                 temperature: float = 0.0, seed: int = 0):
         """wait_levels > 0: before a query the target gives the draft up to wait_ms to have that many
         levels in the cache (for set-ups in which the target is the faster model; the paper's target
-        is several times slower than its draft and never waits: wait_levels = 0)."""
+        is several times slower than its draft and never waits: wait_levels = 0).
+        temperature > 0: the target verifies by sampling (one draw per position from the seeded
+        counter-based generator): the loop then emits the text of token-by-token sampling with that
+        seed, as it emits the greedy text at temperature 0."""
         assert 1 <= K <= 32 and 1 <= k <= 16 and depth >= 1
         self.tgt, self.dr = target, draft
         self.K, self.k, self.depth, self.plant = K, k, depth, plant
         self.r_max = min(depth + 1 if r_max is None else r_max, target.cfg.max_r)
         self.wait_levels, self.wait_ms = wait_levels, wait_ms
+        self.temperature, self.seed = float(temperature), int(seed)
         self.cache = CandidateCache(K=K, max_depth=depth + 1)
         self.lock = threading.Lock()
         self.t_pos = ctx_len          # target: committed context length
@@ -157,7 +162,7 @@ class ConcurrentLoop:
                         time.sleep(0.0001)
                 hit, path, _ = self.cache.query(self.pending, self.r_max)
                 cand = path if hit else [self.pending]
-                res = tgt.verify(self.t_pos, self.pending, cand)
+                res = tgt.verify(self.t_pos, self.pending, cand, temperature=self.temperature, seed=self.seed)
                 a = res["accepted_len"]
                 if a < 1:
                     raise RuntimeError(f"target step failed: {res}")

@@ -226,3 +226,36 @@ def test_concurrent_draft_and_target_on_one_gpu_is_lossless(p, seed, grids):
         assert out["trees_kept_across_corrections"] >= 1
     if p == 0.0:
         assert out["mean_accepted_len"] == 1.0
+
+
+def test_concurrent_loop_at_temperature_one_emits_the_sampled_text():
+    """Temperature 1 in the loop (the paper's T = 1 columns): with the target sampling from the seeded
+    generator, the concurrent loop emits exactly what token-by-token sampling with the same seed
+    emits, whatever the cache offered."""
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape, n_new, seed, T = TINY, 32, 5, 1.0
+    draft_shape = ci.ModelShape("tiny-draft", 1, 128, 2, 1, 64, 344, 1024, ctx=128, r=4)
+    tgt = card.Target(shape, shape.ctx + n_new + 24, grid_wgs=128)
+    load_synthetic_weights(tgt, shape, seed)
+    dr = card.Target(draft_shape, shape.ctx + n_new + 24 + 200, grid_wgs=64)
+    load_synthetic_weights(dr, draft_shape, seed + 100)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, shape.ctx, shape.vocab).tolist()
+    tgt.prefill(ctx[:-1])
+    # the first sampled token: the draw for the position behind the context
+    g0 = tgt.verify(shape.ctx - 1, -1, [ctx[-1]], temperature=T, seed=77)["row_argmax"][0]
+    own, pos = [g0], shape.ctx
+    for _ in range(n_new + 8):
+        own.append(tgt.verify(pos, own[-1], [own[-1]], temperature=T, seed=77)["correction_token"])
+        pos += 1
+    greedy = [g0]
+    for i in range(6):
+        greedy.append(tgt.verify(shape.ctx + i, greedy[-1], [greedy[-1]])["correction_token"])
+    assert greedy != own[:7]  # sampling is not the arg-max here
+    dr.prefill(ctx)
+    loop = card.ConcurrentLoop(tgt, dr, shape.ctx, g0, K=8, k=4, depth=5, r_max=3, wait_levels=2,
+                               plant=card.PlantedAgreement(own, 0.9, seed, shape.vocab), temperature=T, seed=77)
+    out = loop.run(n_new)
+    assert loop.emitted[: n_new + 1] == own[: n_new + 1]
+    assert out["mean_accepted_len"] > 1.3
