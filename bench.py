@@ -435,57 +435,80 @@ def draft_level_entry(args, quick, probe_levels=0):
 
 
 def run_sweep(args, rig8b):
-    """Every synthetic configuration besides the headline one.  rig8b: the headline model, reused."""
+    """Every synthetic configuration besides the headline one.  rig8b: the headline model, reused.
+    A section that fails leaves an entry {"section": ..., "error": ...} and the others still run:
+    the headline line must not depend on a sweep point."""
     import card_inputs as ci
 
     out = []
     quick = args.sweep == "quick"
-    # context sweep on the 8B shape, r = 8
-    for ctx in ([512] if quick else [512, 2048, 8192, 32768]):
-        if ctx + 64 > rig8b.tgt.cfg.max_ctx:
-            continue
-        kind = rig8b.set_context(ctx)
-        out.append(sweep_point(rig8b, 8, 10 if quick else 20, kind))
-    # the target's plain decode rate on the whole GPU (r = 1 steps), the loop's reference
-    rig8b.set_context(256 if quick else 1024)
-    t0 = time.perf_counter()
-    rig8b.greedy(24)
-    decode_tps = 24 / (time.perf_counter() - t0)
+    state = {"decode_tps": None}
+
+    def section(name, fn):
+        try:
+            fn()
+        except Exception as ex:  # noqa: BLE001
+            out.append({"section": name, "error": repr(ex)})
+
+    def ctx_sweep():  # context sweep on the 8B shape, r = 8
+        for ctx in ([512] if quick else [512, 2048, 8192, 32768]):
+            if ctx + 64 > rig8b.tgt.cfg.max_ctx:
+                continue
+            kind = rig8b.set_context(ctx)
+            out.append(sweep_point(rig8b, 8, 10 if quick else 20, kind))
+
+    def decode_8b():  # the target's plain decode rate on the whole GPU (r = 1 steps), the loop's reference
+        rig8b.set_context(256 if quick else 1024)
+        t0 = time.perf_counter()
+        rig8b.greedy(24)
+        state["decode_tps"] = 24 / (time.perf_counter() - t0)
+
+    section("llama8b context sweep", ctx_sweep)
     if quick:
-        out.append(cache_loop(rig8b, 8, 0.6, 16))
-        out += concurrent_loop_entries(args, decode_tps, True)
-        out.append(draft_level_entry(args, True))
+        section("llama8b plain decode", decode_8b)
+        section("cache loop", lambda: out.append(cache_loop(rig8b, 8, 0.6, 16)))
+        section("concurrent loop", lambda: out.extend(concurrent_loop_entries(args, state["decode_tps"], True)))
+        section("draft level", lambda: out.append(draft_level_entry(args, True)))
         return out
     rig8b.close()
-    # Qwen-7B shape, context 4096: r sweep and the shared-cache loop
-    shape = ci.SHAPES["qwen7b"]
-    rig = Rig(shape, args.seed, shape.ctx + 160)
-    kind = rig.set_context(shape.ctx)
-    for r in (1, 2, 4, 8, 16, 32):
-        out.append(sweep_point(rig, r, 20, kind))
-    rig.set_context(2048)  # the loop needs the target's real greedy text: a prefilled context
-    t0 = time.perf_counter()
-    n_dec = 24
-    rig.greedy(n_dec)
-    decode_tps = n_dec / (time.perf_counter() - t0)
-    for p in (0.3, 0.6, 0.9):
-        e = cache_loop(rig, 8, p, 96)
-        e["plain_decode_tokens_per_s"] = decode_tps
-        out.append(e)
-    rig.close()
-    # 70B shape, context 2048
-    shape = ci.SHAPES["llama70b"]
-    rig = Rig(shape, args.seed, shape.ctx)
-    kind = rig.set_context(shape.ctx)
-    for r in (4, 8, 16):
-        out.append(sweep_point(rig, r, 8, kind))
-    rig.set_context(1024)
-    t0 = time.perf_counter()
-    rig.greedy(8)
-    decode_tps = 8 / (time.perf_counter() - t0)  # the 70B target's plain decode rate on the whole GPU
-    rig.close()
-    out += concurrent_loop_entries(args, decode_tps, False)
-    out.append(draft_level_entry(args, False))
+
+    def qwen():  # Qwen-7B shape, context 4096: r sweep and the shared-cache loop
+        shape = ci.SHAPES["qwen7b"]
+        rig = Rig(shape, args.seed, shape.ctx + 160)
+        try:
+            kind = rig.set_context(shape.ctx)
+            for r in (1, 2, 4, 8, 16, 32):
+                out.append(sweep_point(rig, r, 20, kind))
+            rig.set_context(2048)  # the loop needs the target's real greedy text: a prefilled context
+            t0 = time.perf_counter()
+            n_dec = 24
+            rig.greedy(n_dec)
+            decode_tps = n_dec / (time.perf_counter() - t0)
+            for p in (0.3, 0.6, 0.9):
+                e = cache_loop(rig, 8, p, 96)
+                e["plain_decode_tokens_per_s"] = decode_tps
+                out.append(e)
+        finally:
+            rig.close()
+
+    def llama70b():  # 70B shape, context 2048
+        shape = ci.SHAPES["llama70b"]
+        rig = Rig(shape, args.seed, shape.ctx)
+        try:
+            kind = rig.set_context(shape.ctx)
+            for r in (4, 8, 16):
+                out.append(sweep_point(rig, r, 8, kind))
+            rig.set_context(1024)
+            t0 = time.perf_counter()
+            rig.greedy(8)
+            state["decode_tps"] = 8 / (time.perf_counter() - t0)  # the 70B target's plain decode rate on the whole GPU
+        finally:
+            rig.close()
+
+    section("qwen7b r sweep and cache loop", qwen)
+    section("llama70b r sweep", llama70b)
+    section("concurrent loop", lambda: out.extend(concurrent_loop_entries(args, state["decode_tps"], False)))
+    section("draft level", lambda: out.append(draft_level_entry(args, False)))
     return out
 
 

@@ -44,6 +44,7 @@ def test_short_run_prints_one_json_line_with_the_contract_fields(monkeypatch, ca
     assert rf["traffic"] is None or rf["traffic"] >= 0.9 * d["algorithmic_bytes_per_step"]
     # the other synthetic configurations ride in the same line
     sw = d["sweep"]
+    assert not [e for e in sw if "section" in e], [e for e in sw if "section" in e]  # no section failed
     pts = [e for e in sw if e.get("kind") not in ("cache_loop", "concurrent_loop", "draft_level")]
     assert pts and all(e["ms_per_step"] > 0 and 0.1 < e["hbm_frac"] < 1.0 and e["verified_tokens_per_s"] > 0 for e in pts)
     conc = [e for e in sw if e.get("kind") == "concurrent_loop"]
