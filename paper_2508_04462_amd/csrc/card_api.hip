@@ -472,8 +472,9 @@ int card_verify_static(const card_model_cfg* cfg, const void* packed_weights_dev
                        const int32_t* cand_tokens_dev, int32_t r, void* stream, card_verify_result* out_dev,
                        int32_t* row_argmax_dev) {
     const Layout L = make_layout(cfg);
-    if (!L.ok) return CARD_EINVAL;
+    if (!L.ok || !packed_weights_dev || !kv || !cand_tokens_dev || !out_dev) return CARD_EINVAL;
     if (L.ws_bytes > kStaticWsBytes) return CARD_ETOOBIG;
+    if (r < 1 || r > cfg->max_r) return CARD_ERANGE;  // nothing is enqueued for a call that will be refused
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CARD_EDEVICE;
     void* ws = nullptr;

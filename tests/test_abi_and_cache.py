@@ -314,3 +314,38 @@ def test_the_draft_loop_rerooting_of_its_own_tree_record_follows_the_cache(seed)
             # slots and rows travelled with their nodes
             for lv in loop.mirror:
                 assert all(r[1] == s % 1000 for r, s in zip(lv.row, lv.slot))
+
+
+def test_argument_errors_of_the_later_entry_points_are_caught_on_the_host():
+    """Sampled, static, draft-level and selection calls refuse bad arguments before anything is
+    enqueued (fake device addresses: nothing here may reach a launch)."""
+    cfg = card.make_cfg(ci.SHAPES["tiny"], 256)
+    kv = card.CardKV(0x1000, 0x1000, 0x1000, 16, -1)
+    P = 0x1000
+    # sampling: the temperature must be a number >= 0
+    assert card.card_verify_sampled(cfg, P, kv, 0, P, 4, card.CardSampling(-1.0, 0), P, None, P) == card.CARD_EINVAL
+    assert card.card_verify_sampled(cfg, P, kv, 0, P, 4, card.CardSampling(float("nan"), 0), P, None, P) == card.CARD_EINVAL
+    assert card.card_verify_sampled(cfg, P, kv, 0, P, 40, card.CardSampling(1.0, 0), P, None, P) == card.CARD_ERANGE
+    # the entry point without allocation refuses a model whose workspace exceeds its scratch array
+    big = card.make_cfg(ci.SHAPES["llama70b"], 4096)
+    assert card.card_workspace_bytes(big) > card.card_static_scratch_bytes()
+    assert card.card_verify_static(big, P, kv, 0, P, 4, None, P) == card.CARD_ETOOBIG
+    assert card.card_verify_static(cfg, None, kv, 0, P, 4, None, P) == card.CARD_EINVAL
+    assert card.card_verify_static(cfg, P, kv, 0, P, 0, None, P) == card.CARD_ERANGE
+    # draft level: k, mask geometry, slots
+    def rows(first, words, base):
+        return card.CardTreeRows(P, P, first, P, words, base)
+    tk = P
+    assert card.card_draft_level(cfg, P, kv, 64, rows(64, 2, 64), 4, 0, P, None, tk, P) == card.CARD_ERANGE      # k = 0
+    assert card.card_draft_level(cfg, P, kv, 64, rows(64, 2, 64), 4, 17, P, None, tk, P) == card.CARD_ERANGE     # k > 16
+    assert card.card_draft_level(cfg, P, kv, 64, rows(64, 33, 64), 4, 4, P, None, tk, P) == card.CARD_ERANGE     # 33 mask words
+    assert card.card_draft_level(cfg, P, kv, 64, rows(64, 2, 60), 4, 4, P, None, tk, P) == card.CARD_EINVAL      # base off a page
+    assert card.card_draft_level(cfg, P, kv, 64, rows(64, 2, 80), 4, 4, P, None, tk, P) == card.CARD_EINVAL      # base behind the context
+    assert card.card_draft_level(cfg, P, kv, 64, rows(60, 2, 48), 4, 4, P, None, tk, P) == card.CARD_ERANGE      # slot inside the context
+    assert card.card_draft_level(cfg, P, kv, 64, rows(126, 2, 64), 4, 4, P, None, tk, P) == card.CARD_ERANGE     # rows past the mask
+    assert card.card_draft_level(cfg, P, kv, 64, rows(254, 8, 64), 4, 4, P, None, tk, P) == card.CARD_ECAPACITY  # past max_ctx
+    assert card.card_draft_level(cfg, P, kv, 64, rows(64, 2, 64), 4, 4, P, None, None, P) == card.CARD_EINVAL
+    # selection
+    assert card.card_cache_select(P, P, P, 0, 4, 8, P, P, P) == card.CARD_ERANGE
+    assert card.card_cache_select(P, P, P, 200, 16, 8, P, P, P) == card.CARD_ERANGE  # more than 2048 tuples
+    assert card.card_cache_select(P, None, P, 4, 4, 8, P, P, P) == card.CARD_EINVAL
