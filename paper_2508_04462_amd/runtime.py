@@ -149,9 +149,10 @@ class CandidateCache:
         self.K = K
 
     def __del__(self):
-        if getattr(self, "h", None):
-            B.card_cache_destroy(self.h)
-            self.h = None
+        h, self.h = getattr(self, "h", None), None
+        destroy = getattr(B, "card_cache_destroy", None)  # module globals may be gone at interpreter exit
+        if h and destroy is not None:
+            destroy(h)
 
     def write(self, level: int, tokens, parents, scores, epoch: Optional[int] = None) -> int:
         return B.card_cache_write(self.h, self.epoch() if epoch is None else epoch, level, tokens, parents, scores)
