@@ -327,8 +327,9 @@ int card_cache_read_level(const card_cache* c, int32_t level, int32_t* tokens, i
  * w = prob[i][j] * sigma[i] (sigma: cumulative probability of parent i's sequence, eq. (4)),
  * pools the n_parents * k tuples (eq. (5)), sorts them by score (eq. (6)) and keeps the K best
  * (eq. (7)): out_tokens / out_scores / out_parents [K], best first, equal scores by (parent, rank).
- * n_parents * k <= 2048.  Entries of topk_tokens_dev that are negative are skipped.  Returns the
- * number of tuples written, min(K, n_parents * k), or a negative status.  Appending token m to
+ * n_parents * k <= 2048.  Entries of topk_tokens_dev that are negative are skipped; if fewer than
+ * the returned count remain, the outputs behind them are marked empty (token -1, score 0, parent
+ * -1).  Returns the number of entries written, min(K, n_parents * k), or a negative status.  Appending token m to
  * parent m's sequence (eqs. (8)-(9)) is what card_cache_write stores from these arrays.
  * ---------------------------------------------------------------------------------------- */
 /* Host helper, Mask Construction for Draft Model: the mask rows of one level from the rows of

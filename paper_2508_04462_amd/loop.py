@@ -338,6 +338,11 @@ class ConcurrentLoop:
                     raise B.CardError(cnt, "card_cache_select")
                 stream.synchronize()
                 nt, npar, ns = ot[:cnt].tolist(), op[:cnt].tolist(), os_[:cnt].tolist()
+                if -1 in nt:  # fewer tuples than K below the nodes that are left: the rest is marked empty
+                    cnt = nt.index(-1)
+                    nt, npar, ns = nt[:cnt], npar[:cnt], ns[:cnt]
+                if cnt == 0:
+                    raise RuntimeError("no extension below the verified token")
                 if self.plant is not None:
                     nt, npar = self.plant(root_index + D + 1, D + 1, nt, npar)
                 if self.stop or self.cache.write(D + 1, nt, npar, ns, epoch=epoch) != B.CARD_OK:

@@ -123,6 +123,20 @@ def test_select_exact_on_dyadic_scores_with_ties():
         assert n == min(K, M * k) == len(rt)
         assert ot[:n].tolist() == rt.tolist() and op[:n].tolist() == rp.tolist()
         np.testing.assert_array_equal(os_[:n].cpu().numpy().astype(np.float64), rs)
+    # parents switched off by a negative token take no part; outputs behind the last tuple are marked empty
+    M, k, K, dev = 6, 3, 8, "cuda:0"
+    toks = torch.arange(M * k, dtype=torch.int32, device=dev).reshape(M, k)
+    toks[[0, 1, 3, 5]] = -1
+    pv = torch.tensor([[0.5, 0.25, 0.125]] * M, dtype=torch.float32, device=dev)
+    sigma = torch.tensor([1.0, 1.0, 0.5, 1.0, 1.0, 1.0], dtype=torch.float32, device=dev)
+    ot = torch.empty(K, dtype=torch.int32, device=dev)
+    os_ = torch.empty(K, dtype=torch.float32, device=dev)
+    op = torch.empty(K, dtype=torch.int32, device=dev)
+    assert card.card_cache_select(sigma, toks, pv, M, k, K, ot, os_, op) == K
+    torch.cuda.synchronize()
+    # equal scores: the lower parent index first
+    assert ot.tolist() == [12, 6, 13, 7, 14, 8, -1, -1] and op.tolist() == [4, 2, 4, 2, 4, 2, -1, -1]
+    assert os_.tolist() == [0.5, 0.25, 0.25, 0.125, 0.125, 0.0625, 0.0, 0.0]
     bad = torch.zeros(4, dtype=torch.int32, device="cuda:0")
     assert card.card_cache_select(bad, bad, bad, 200, 16, 10, bad, bad, bad) == card.CARD_ERANGE
 
