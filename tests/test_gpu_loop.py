@@ -259,3 +259,35 @@ def test_concurrent_loop_at_temperature_one_emits_the_sampled_text():
     out = loop.run(n_new)
     assert loop.emitted[: n_new + 1] == own[: n_new + 1]
     assert out["mean_accepted_len"] > 1.3
+
+
+def test_concurrent_loop_with_a_draft_that_runs_ahead_of_its_target():
+    """The paper's regime: the target (8B-shaped, on 192 workgroups) is several times slower than the
+    draft (a small model on 64), so the draft builds levels while a verification is in flight, keeps
+    its tree across the corrections and the target finds a path below its own token most of the
+    time.  The emitted text is the target's plain decode; K = 24 with top-4 per node also takes the
+    levels that have fewer extensions than K."""
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape, seed, ctx_len, n_new = ci.SHAPES["llama8b"], 3, 256, 96
+    draft_shape = ci.ModelShape("small-draft", 2, 512, 8, 2, 64, 1376, shape.vocab, ctx=128, r=4)
+    tgt = card.Target(shape, ctx_len + n_new + 64, grid_wgs=192)
+    load_synthetic_weights(tgt, shape, seed)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, ctx_len, shape.vocab).tolist()
+    g0 = tgt.prefill(ctx)
+    own, pos = [g0], ctx_len
+    for _ in range(n_new + 16):
+        own.append(tgt.verify(pos, own[-1], [own[-1]])["correction_token"])
+        pos += 1
+    for K, dmax in ((8, ctx_len + n_new + 1100), (24, ctx_len + n_new + 360)):  # the second: tree slots run out
+        dr = card.Target(draft_shape, dmax, grid_wgs=64)
+        load_synthetic_weights(dr, draft_shape, seed + 100)
+        dr.prefill(ctx)
+        loop = card.ConcurrentLoop(tgt, dr, ctx_len, g0, K=K, k=4, depth=12, r_max=8,
+                                   plant=card.PlantedAgreement(own, 0.95, seed, shape.vocab))
+        out = loop.run(n_new)
+        assert loop.emitted[: n_new + 1] == own[: n_new + 1]
+        assert out["mean_accepted_len"] > 2.5 and out["hit_rate"] > 0.6, out
+        assert out["trees_kept_across_corrections"] > out["draft_restarts"], out
+        assert out["draft_levels_per_target_step"] > 2.0, out
