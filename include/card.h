@@ -151,7 +151,8 @@ typedef struct card_verify_result {
  * row i-1's vocabulary logits.  Logits are never written to memory.
  *   packed_weights_dev : blob filled by card_weights_pack_tensor
  *   kv                 : host struct (read during the call only)
- *   cand_tokens_dev    : dev, r int32 token ids in [0, vocab)
+ *   cand_tokens_dev    : dev (or device-visible pinned host memory, as card_step_begin uses:
+ *                        the kernel reads the ids itself), r int32 token ids in [0, vocab)
  *   workspace_dev      : dev, card_workspace_bytes(cfg) bytes, prepared by card_workspace_init
  *                        once after allocation (and again after a call reported CARD_EDEVICE or
  *                        accepted_len < 0); calls sharing a workspace must not overlap
