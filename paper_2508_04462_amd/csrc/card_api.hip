@@ -228,6 +228,8 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     a.best = reinterpret_cast<unsigned long long*>(ws + L.m_best_off);
     a.bar = reinterpret_cast<uint32_t*>(ws + L.m_bar_off);
     a.acount = reinterpret_cast<uint32_t*>(ws + L.m_acount_off);
+    a.dpart = reinterpret_cast<float*>(ws + L.m_dpart_off);
+    a.dcount = reinterpret_cast<uint32_t*>(ws + L.m_dcount_off);
     a.flags = reinterpret_cast<uint32_t*>(ws + L.m_flags_off);
     a.cand = cand;
     if (tree) {

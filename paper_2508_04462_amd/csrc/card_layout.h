@@ -77,7 +77,8 @@ struct Layout {
     size_t ws_bytes;
     // workspace of the persistent kernel (byte offsets) and strides in elements
     size_t m_xres_off, m_xfrag_off, m_ss_off, m_qfrag_off, m_attfrag_off, m_actfrag_off, m_apart_off, m_bar_off,
-        m_acount_off, m_flags_off, m_best_off, m_rope_off, m_topk_off, m_lse_off, m_out_off;
+        m_acount_off, m_flags_off, m_best_off, m_rope_off, m_topk_off, m_lse_off, m_out_off, m_dpart_off,
+        m_dcount_off;
     size_t xfrag_stride, attfrag_stride, actfrag_stride, qfrag_stride;
     int32_t m_attn_max_splits;
 };
@@ -178,6 +179,11 @@ inline Layout make_layout(const card_model_cfg* c) {
     L.m_topk_off = take(size_t(256) * kMaxR * 16 * 8);  // per workgroup and row: sixteen best keys
     L.m_lse_off = take(size_t(256) * kMaxR * 2 * 4);    // per workgroup and row: (max, sum of exp)
     L.m_out_off = take(64);                             // where a draft-side call parks the verify result
+    // down-projection at r > 8: the four workgroups of a group each hold a quarter of K of the
+    // group's tiles; per tile four partial blocks of 16 x 32 fp32, and one arrival counter per
+    // four tiles
+    L.m_dpart_off = take(size_t(L.wd.Nt) * kStreamWaves * 16 * kMaxR * 4);
+    L.m_dcount_off = take(size_t(ceil_div(L.wd.Nt, 4)) * 4);
     L.ws_bytes = w;
     L.ok = true;
     return L;

@@ -75,6 +75,8 @@ struct MegaArgs {
     uint32_t* bar;     // kBarExit, kBarError (zero between calls), kBarEpoch, kBarMagic
     uint32_t* flags;   // [kFlagCopies][256] last barrier sequence number each workgroup has reached
     uint32_t* acount;  // [Hkv * row_tiles] arrival counters of the attention cuts; zero between uses
+    float* dpart;      // [d/16 tiles][4 quarters of K][16][32] partial down-projection blocks (r > 8)
+    uint32_t* dcount;  // [d/64] arrival counters of the groups of four tiles; zero between uses
     const int32_t* cand;
     // draft-side tree rows (all zero / null for a verification step): row m sits at sequence position
     // row_pos[m] and in cache slot slot0 + m; it sees every slot below tmask_base and, from there on,
@@ -254,6 +256,10 @@ struct PhasePlan {
     const bf16x8* w;
     uint32_t bytes, first;
     int32_t Ks, Nt, t_first, cnt, s0, s1;
+    // grouped plan only (plan_phase_grouped): bytes from a tile's fragment to the next tile's of the
+    // same k-step, bytes from one batch's first fragment to the next batch's, the workgroup's quarter
+    uint32_t stride, batch_skip;
+    int32_t quarter;
 };
 
 __device__ __forceinline__ PhasePlan plan_phase(const bf16x8* w, int Nt, int Ks, int wg, int nwg, int rot, int wave) {
@@ -268,15 +274,53 @@ __device__ __forceinline__ PhasePlan plan_phase(const bf16x8* w, int Nt, int Ks,
     p.s0 = r.s0;
     p.s1 = r.s1;
     p.first = uint32_t(r.first) << 10;
+    p.stride = 0u;
+    p.batch_skip = 0u;
+    p.quarter = 0;
+    return p;
+}
+
+// The same matrix, the same packed order, another division of the work, for phases in which a
+// workgroup owns a single tile and r > 8: there every wavefront pulls r/8 KiB of activations
+// through the vector L1 per KiB of weights, and that path, not HBM, sets the pace.  Four
+// workgroups whose grid positions differ in the last two bits form a group and share the
+// group's tiles (one per position and batch): position 4g + j takes the j-th quarter of K of
+// all four tiles, its wavefront pair i the i-th quarter of that.  A wavefront then uses every
+// activation operand for four tiles (a quarter of the L1 traffic per weight fragment), a pair
+// streams four runs (one per tile, `stride` bytes apart) interleaved k-step by k-step, and the
+// four workgroups' partial sums meet in memory.  Needs the four positions of a group to own
+// equally many tiles: tile count and grid size multiples of four.
+__device__ __forceinline__ PhasePlan plan_phase_grouped(const bf16x8* w, int Nt, int Ks, int wg, int nwg, int rot, int wave) {
+    PhasePlan p;
+    p.w = w;
+    p.bytes = uint32_t(Nt) * uint32_t(Ks) * 1024u;
+    p.Ks = Ks;
+    p.Nt = Nt;
+    const int pos = (wg + rot) % nwg, g0 = pos & ~3;
+    p.quarter = pos & 3;
+    const StreamRun q = stream_run(Nt, Ks, nwg, g0, p.quarter);  // the quarter's run of position g0
+    const int len = q.s1 - q.s0;
+    p.s0 = q.s0 + (wave * len) / kStreamWaves;
+    p.s1 = q.s0 + ((wave + 1) * len) / kStreamWaves;
+    p.t_first = g0;
+    p.cnt = 4 * q.cnt;
+    p.first = uint32_t(q.first + (p.s0 - q.s0)) << 10;
+    p.stride = (uint32_t(q.cnt) * uint32_t(Ks)) << 10;  // a position's region of the matrix
+    p.batch_skip = uint32_t(len) << 10;
     return p;
 }
 
 enum StreamPhase { SP_QKV = 0, SP_WO = 1, SP_GU = 2, SP_WD = 3 };
 
+// Whether the down-projection runs in groups of four workgroups (kernels for r > 8 only): the
+// rotation by half the grid has to keep groups together.
+__device__ __forceinline__ bool down_grouped(const MegaArgs& a) { return (a.nwg & 7) == 0 && (a.wd.Nt & 3) == 0; }
+
 // Phase number ph = 4 * layer + StreamPhase, or 4 * L for the vocabulary head.  The one place
 // that says which matrix and which tile rotation a phase has: producers and consumers both ask
 // here.  (Workgroups with one tile more than the others alternate between the halves of the
 // grid from layer to layer.)
+template <bool GROUPED>
 __device__ __forceinline__ PhasePlan stream_phase(const MegaArgs& a, int ph, int wg, int wave) {
     const int nwg = a.nwg;
     if (ph >= 4 * a.L)
@@ -290,6 +334,11 @@ __device__ __forceinline__ PhasePlan stream_phase(const MegaArgs& a, int ph, int
         return plan_phase(reinterpret_cast<const bf16x8*>(lb + a.wo.off), a.wo.Nt, a.wo.Ks, wg, nwg, (l & 1) * half, wave);
     if (k == SP_GU)
         return plan_phase(reinterpret_cast<const bf16x8*>(lb + a.gu.off), a.gu.Nt, a.gu.Ks, wg, nwg, 0, wave);
+    if constexpr (GROUPED) {
+        if (down_grouped(a))
+            return plan_phase_grouped(reinterpret_cast<const bf16x8*>(lb + a.wd.off), a.wd.Nt, a.wd.Ks, wg, nwg,
+                                      ((l + 1) & 1) * half, wave);
+    }
     return plan_phase(reinterpret_cast<const bf16x8*>(lb + a.wd.off), a.wd.Nt, a.wd.Ks, wg, nwg, ((l + 1) & 1) * half, wave);
 }
 
@@ -303,41 +352,93 @@ __device__ __forceinline__ PhasePlan stream_phase(const MegaArgs& a, int ph, int
 // refill, and a fragment is due every ~150 ns: the per-fragment path is a few dozen instructions
 // without a taken branch (the next address is the last one + 1 KiB: stream order), everything
 // else happens once per phase or when the FIFO is full.
+//
+// GROUPED (the kernels for r > 8): a phase planned by plan_phase_grouped interleaves four runs, one
+// per tile of the batch.  The ring is unrolled, slot j always holds stream index n = j (mod 8), so
+// the fragment with stream index n carries tile n & 3 (a fixed offset per ring slot: no counter,
+// no select), and the k-step offset moves on behind the fourth fragment of a k-step, which is the
+// slot with n & 3 == (rho + 3) & 3, rho = stream index of the phase's first fragment & 3.  The
+// consumer, which has the same count, knows rho and which tile each of its accumulators holds.
+// Plain phases are the same code with zero tile offsets and a step behind every fragment: one
+// scalar addition more per fragment than the kernels for r <= 8 have.
+template <bool GROUPED>
 __device__ __forceinline__ void producer(const MegaArgs& a, MegaSmem& sm, int w, int lane, int wg) {
     const int n_ph = 4 * a.L + 1;
     int ph = -1;
     // the next load: resource, scalar offset, fragments left in the phase (0: the stream has ended)
     __amdgpu_buffer_rsrc_t cur_rs = make_rsrc(a.wbase, 0);
-    uint32_t cur_off = 0, left = 0;
+    uint32_t cur_off = 0, left = 0, issued = 0;
+    uint32_t tile_off[4] = {0u, 0u, 0u, 0u}, step_behind[4] = {1024u, 1024u, 1024u, 1024u};
+    uint32_t batches_left = 0u, per_batch = 0u, batch_base = 0u, batch_skip = 0u;
     auto next_phase = [&]() {
+        if constexpr (GROUPED) {
+            if (batches_left != 0u) {  // the next batch of a grouped phase
+                --batches_left;
+                batch_base += batch_skip;
+                cur_off = batch_base;
+                left = per_batch;
+                return;
+            }
+        }
         while (++ph < n_ph) {
-            const PhasePlan P = stream_phase(a, ph, wg, w);
+            const PhasePlan P = stream_phase<GROUPED>(a, ph, wg, w);
             left = uint32_t(P.cnt) * uint32_t(P.s1 - P.s0);
             if (left == 0) continue;
             cur_rs = make_rsrc(P.w, P.bytes);
             cur_off = P.first;
+            if constexpr (GROUPED) {
+                if (P.stride != 0u) {
+                    const uint32_t last = (issued + 3u) & 3u;  // `issued` already counts the fragment before this phase
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        tile_off[u] = uint32_t(u) * P.stride;
+                        step_behind[u] = uint32_t(u) == last ? 1024u : 0u;
+                    }
+                    per_batch = 4u * uint32_t(P.s1 - P.s0);
+                    batches_left = left / per_batch - 1u;
+                    left = per_batch;
+                    batch_base = P.first;
+                    batch_skip = P.batch_skip;
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        tile_off[u] = 0u;
+                        step_behind[u] = 1024u;
+                    }
+                    batches_left = 0u;
+                }
+            }
             if (a.ts && w == 0 && lane == 0 && (ph >> 2) == a.ts_layer) a.ts[size_t(wg) * 32 + 17 + (ph & 3)] = wall_clock64();
             return;
         }
         left = 0;
         cur_off = 0;
+        if constexpr (GROUPED) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) tile_off[u] = 0u;
+        }
     };
     next_phase();
-    uint32_t issued = 0, pushed = 0, head_seen = 0, pofs = 0;
+    uint32_t pushed = 0, head_seen = 0, pofs = 0;
     bool dead = false;
     // Every ring step is the same straight line on every path: wait for the slot's load, write it
     // to LDS (to a dump slot once the stream has ended), issue the slot's next load (an out-of-range
     // lane offset once the stream has ended: zeros, no memory access).  The scalar bookkeeping in
     // between may branch, the memory operations never do: the compiler's wait in front of a slot's
     // use then leaves exactly the other kRing - 1 loads in flight.
-    auto issue = [&](bf16x8& dst) {
+    auto issue = [&](bf16x8& dst, int slot) {
         const bool real = left != 0;
         int voff = real ? lane * 16 : kOutOfRange;
-        asm volatile("" : "+s"(cur_off), "+v"(voff));  // one load here, not one per incoming path
-        dst = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(cur_rs, voff, int(cur_off), kAuxNT));
+        uint32_t soff = cur_off;
+        if constexpr (GROUPED) soff += tile_off[slot & 3];
+        asm volatile("" : "+s"(soff), "+v"(voff));  // one load here, not one per incoming path
+        dst = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(cur_rs, voff, int(soff), kAuxNT));
         if (real) {
             ++issued;
-            cur_off += 1024u;
+            if constexpr (GROUPED)
+                cur_off += step_behind[slot & 3];
+            else
+                cur_off += 1024u;
             if (__builtin_expect(--left == 0, 0)) next_phase();
         }
     };
@@ -367,12 +468,12 @@ __device__ __forceinline__ void producer(const MegaArgs& a, MegaSmem& sm, int w,
     };
     bf16x8 rg[kRing];
 #pragma unroll
-    for (int j = 0; j < kRing; ++j) issue(rg[j]);
+    for (int j = 0; j < kRing; ++j) issue(rg[j], j);
     while (pushed < issued) {
 #pragma unroll
         for (int j = 0; j < kRing; ++j) {
             push(rg[j]);
-            issue(rg[j]);
+            issue(rg[j], j);
         }
     }
 }
@@ -473,7 +574,14 @@ struct NoHook {
 // instruction per weight fragment does what otherwise takes two, one operand load per k-step
 // fetches the whole contiguous rp*128-byte run, and the two partial products of a row meet in the
 // reduction.  (The ring stays eight k-steps deep: sixteen measured 3 % slower.)
-template <int NB, int MT, int EPI, bool PK, typename Hook = NoHook>
+//
+// GRP4 (r > 8, residual epilogue): the phase was planned by plan_phase_grouped.  The batch's four
+// tiles belong to the four positions of the group (tile ids t_first + i, the next batch nwg
+// further on); what the workgroup has after its own reduction is the sum over ITS quarter of K,
+// so the four workgroups hand their blocks over in memory and the last one to arrive adds the four
+// (always in the order of the quarters, whoever comes last) and runs the epilogue for all four
+// tiles.
+template <int NB, int MT, int EPI, bool PK, typename Hook = NoHook, bool GRP4 = false>
 __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P, const __bf16* xf, uint32_t xf_bytes,
                                            const EpiArgs& ea, FifoC& fc, MegaSmem& sm, int wave, int lane,
                                            uint32_t& cgen, Hook after_k = Hook()) {
@@ -487,6 +595,11 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
     // k-steps in the activation ring (a multiple of SG): eight single-operand steps, four
     // two-operand steps, two four-operand steps
     static_assert(!PK || MT == 1, "packed halves: one row tile");
+    static_assert(!GRP4 || (!PK && NB == 4 && EPI == ME_RESID), "grouped phases: four tiles, residual epilogue");
+    const int t_inner = GRP4 ? 1 : a.nwg, t_batch = GRP4 ? a.nwg : NB * a.nwg;  // tile id steps inside a batch, between batches
+    // grouped phases: the fragment with stream index n carries tile n & 3, so accumulator i of this
+    // wavefront holds tile (i + rho) & 3, rho = stream index of the phase's first fragment & 3
+    const uint32_t rho = GRP4 ? (fc.head & 3u) : 0u;
     constexpr int XD = PK ? 8 : (MT == 2 ? 2 : 4);
     static_assert(XD % SG == 0, "ring of whole groups");
     constexpr int COLS = 16 * MT;
@@ -561,7 +674,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
 #pragma unroll
         for (int e = 0; e < 8; ++e) xo8[e] = gn8[e] = 0.f;
         if (on) {
-            const int n0 = (P.t_first + i * a.nwg) * 16 + c * 8;
+            const int n0 = (P.t_first + i * t_inner) * 16 + c * 8;
             const float4 x0 = *reinterpret_cast<const float4*>(ea.xres_old + size_t(m) * a.d + n0);
             const float4 x1 = *reinterpret_cast<const float4*>(ea.xres_old + size_t(m) * a.d + n0 + 4);
             const float4 g0 = *reinterpret_cast<const float4*>(ea.gain_next + n0);
@@ -678,7 +791,8 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
         for (int i = 0; i < NBS; ++i)
 #pragma unroll
             for (int j = 0; j < MT; ++j)
-                *reinterpret_cast<floatx4*>(&sm.red[(wave * NBS * MT + i * MT + j) * 256 + lane * 4]) = acc[sb * NBS + i][j];
+                *reinterpret_cast<floatx4*>(&sm.red[(wave * NBS * MT + (GRP4 ? int((uint32_t(i) + rho) & 3u) : i) * MT + j) * 256 +
+                                                    lane * 4]) = acc[sb * NBS + i][j];
         cbar(sm, cgen);
         for (int e = tid; e < NBS * MT * 256; e += kMegaThreads) {
             float s = 0.f;
@@ -697,14 +811,63 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
         cbar(sm, cgen);
 
         // ---- epilogue ----------------------------------------------------------------------------
-        const int tile0 = P.t_first + (b * NB + sb * NBS) * a.nwg;  // tile i of the sub-batch: tile0 + i * nwg
+        const int tile0 = P.t_first + b * t_batch + sb * NBS * t_inner;  // tile i of the sub-batch: tile0 + i * t_inner
+        bool finish = true;
+        if constexpr (GRP4) {
+            // this workgroup's block (its quarter of K, the batch's four tiles) goes to memory ...
+            constexpr int BLK = 4 * 16 * kMaxR;  // floats per (group of four tiles, quarter)
+            constexpr int NEL = NB * 16 * COLS;  // of which this kernel uses
+            float* grp = a.dpart + size_t(tile0 >> 2) * (4 * BLK);
+            const int e0 = tid * 8;
+            if (e0 < NEL) {
+                float v8[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) v8[q] = sm.tile[e0 + q];
+                st_dev_f32x8(grp + P.quarter * BLK, e0, v8);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);
+            cbar(sm, cgen);
+            int* flag = reinterpret_cast<int*>(&sm.wgt[(kMegaWaves + 2) * 16]);
+            if (tid == 0) {
+                const uint32_t prev = __hip_atomic_fetch_add(&a.dcount[tile0 >> 2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                *flag = prev == 3u;
+            }
+            cbar(sm, cgen);
+            finish = *flag != 0;
+            if (finish) {
+                // ... and the last of the four adds them up, quarter by quarter
+                const __amdgpu_buffer_rsrc_t prs = make_rsrc(grp, 4 * BLK * 4);
+                if (e0 < NEL) {
+                    uint4v lo4[4], hi4[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        lo4[q] = __builtin_amdgcn_raw_buffer_load_b128(prs, e0 * 4, q * BLK * 4, kAuxDev);
+                        hi4[q] = __builtin_amdgcn_raw_buffer_load_b128(prs, e0 * 4 + 16, q * BLK * 4, kAuxDev);
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            s0 += __uint_as_float(lo4[q][v]);
+                            s1 += __uint_as_float(hi4[q][v]);
+                        }
+                        sm.tile[e0 + v] = s0;
+                        sm.tile[e0 + 4 + v] = s1;
+                    }
+                }
+                if (tid == 0) __hip_atomic_store(&a.dcount[tile0 >> 2], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                cbar(sm, cgen);
+            }
+        }
         if constexpr (EPI == ME_RESID) {
             // work item: (tile i, row m, half c of the 16 columns); lanes 2q and 2q+1 share a row
             const int c = tid & 1, m = (tid >> 1) % kMaxR, i = tid / (2 * kMaxR);
-            const bool on = i < nvalid_s && m < r;
+            const bool on = i < nvalid_s && m < r && finish;
             float ssum = 0.f;
             if (on) {
-                const int n0 = (tile0 + i * a.nwg) * 16 + c * 8;
+                const int n0 = (tile0 + i * t_inner) * 16 + c * 8;
                 if (b > 0) {  // later batches were not pre-loaded
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
@@ -723,7 +886,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
                 st_dev_frag8(ea.xfrag_new, frag_index(n0, m, rp), gv);
             }
             ssum += __shfl_xor(ssum, 1);
-            if (on && c == 0) st_agent(ea.ss_new + size_t(m) * (a.d >> 4) + (tile0 + i * a.nwg), ssum);
+            if (on && c == 0) st_agent(ea.ss_new + size_t(m) * (a.d >> 4) + (tile0 + i * t_inner), ssum);
             static_assert(NBS * 2 * kMaxR <= kMegaThreads, "one pass");
         } else if constexpr (EPI == ME_SWIGLU) {
             const int m = tid % kMaxR, i = tid / kMaxR;
@@ -1376,7 +1539,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
     }
 
     if (wave >= kMegaWaves) {
-        producer(a, sm, wave - kMegaWaves, lane, wg);
+        producer<!PK>(a, sm, wave - kMegaWaves, lane, wg);
         return;
     }
 
@@ -1441,7 +1604,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         // QKV (+norm scale, rotation, KV write).  Pages that hold only old context do not depend
         // on this phase: their loads are issued as soon as the k-loop is over, ahead of the
         // epilogue's stores, and land while the barrier in front of attention is crossed.
-        const PhasePlan p_qkv = stream_phase(a, 4 * l + SP_QKV, wg, wave);
+        const PhasePlan p_qkv = stream_phase<!PK>(a, 4 * l + SP_QKV, wg, wave);
         ea.ss_in = a.ss + v0 * ss_stride;
         ea.qfrag = a.qfrag + size_t(l) * a.qfrag_stride;
         ea.kpool = a.kpool + size_t(l) * a.pool_layer_elems;
@@ -1477,7 +1640,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         CARD_TS(4)
 
         // O-projection + residual -> version v1, gained with the FFN norm's gain
-        const PhasePlan p_wo = stream_phase(a, 4 * l + SP_WO, wg, wave);
+        const PhasePlan p_wo = stream_phase<!PK>(a, 4 * l + SP_WO, wg, wave);
         ea.xres_old = a.xres + v0 * xres_stride;
         ea.xres_new = a.xres + v1 * xres_stride;
         ea.xfrag_new = a.xfrag + v1 * a.xfrag_stride;
@@ -1492,7 +1655,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         CARD_TS(6)
 
         // gate/up + SwiGLU
-        const PhasePlan p_gu = stream_phase(a, 4 * l + SP_GU, wg, wave);
+        const PhasePlan p_gu = stream_phase<!PK>(a, 4 * l + SP_GU, wg, wave);
         ea.ss_in = a.ss + v1 * ss_stride;
         ea.actfrag = a.actfrag + size_t(l) * a.actfrag_stride;
         ea.ts0 = 0;
@@ -1504,7 +1667,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         CARD_TS(8)
 
         // down + residual -> version v2, gained with the next norm's gain
-        const PhasePlan p_wd = stream_phase(a, 4 * l + SP_WD, wg, wave);
+        const PhasePlan p_wd = stream_phase<!PK>(a, 4 * l + SP_WD, wg, wave);
         ea.xres_old = a.xres + v1 * xres_stride;
         ea.xres_new = a.xres + v2 * xres_stride;
         ea.xfrag_new = a.xfrag + v2 * a.xfrag_stride;
@@ -1512,8 +1675,17 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
         ea.gain_next = last ? reinterpret_cast<const float*>(a.wbase + a.g_final_off)
                             : reinterpret_cast<const float*>(layer_base(l + 1) + a.g_attn_off);
         ea.ts0 = 27;
-        gemm_phase<kNbOne, MT, ME_RESID, PK>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride,
-                                            uint32_t(a.actfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
+        if constexpr (!PK) {
+            if (down_grouped(a))
+                gemm_phase<4, MT, ME_RESID, false, NoHook, true>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride,
+                                                                 uint32_t(a.actfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
+            else
+                gemm_phase<kNbOne, MT, ME_RESID, false>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride,
+                                                        uint32_t(a.actfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
+        } else {
+            gemm_phase<kNbOne, MT, ME_RESID, PK>(a, p_wd, a.actfrag + size_t(l) * a.actfrag_stride,
+                                                uint32_t(a.actfrag_stride * 2), ea, fc, sm, wave, lane, cgen);
+        }
         CARD_TS(9)
         store_wait();
         grid_wait(a, gen, sm, cgen);
@@ -1522,7 +1694,7 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2
 
     // vocabulary head + arg-max
     {
-                const PhasePlan p_lm = stream_phase(a, 4 * a.L, wg, wave);
+                const PhasePlan p_lm = stream_phase<!PK>(a, 4 * a.L, wg, wave);
         EpiArgs ea = {};
         ea.ss_in = a.ss + size_t(2 * a.L) * ss_stride;
         LmState lm = {{0ull, 0ull}, -1e30f, 0.f};
