@@ -127,6 +127,30 @@ def test_shapes_mid_model(r, ctx_len):
     assert np.abs(k.numpy() - ref_k).max() <= 2.0 ** -7 * np.abs(ref_k).max()
 
 
+@pytest.mark.parametrize("grid,r", [(8, 32), (24, 16), (100, 20), (252, 12), (64, 9), (192, 8)])
+def test_grids_of_other_sizes(grid, r):
+    """The caller chooses the grid (cfg.grid_wgs).  Multiples of eight run the down-projection of
+    the r > 8 kernels in groups of four workgroups (on 8 and 24 workgroups every position owns
+    several tiles: several batches per group), other sizes run it one tile per workgroup; the
+    result is the oracle's either way."""
+    import paper_2508_04462_amd as card
+    from oracle.from_inputs import oracle_weights
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape, seed, ctx_len = MID, 13, 45
+    tgt = card.Target(shape, 128, max_r=32, grid_wgs=grid)
+    load_synthetic_weights(tgt, shape, seed, 0.2)
+    w = oracle_weights(shape, seed, 0.2)
+    toks = ci.uniform_tokens(seed, "ctx_tokens", r, ctx_len + r, shape.vocab).tolist()
+    kv = co.OracleKV.empty(shape, 128)
+    co.prefill(shape, w, kv, toks[:ctx_len])
+    tgt.prefill(toks[:ctx_len], chunk=32)
+    ref = co.verify(shape, w, kv, ctx_len, -1, toks[ctx_len:], keep_logits=True)
+    res = tgt.verify(ctx_len, -1, toks[ctx_len:], want_logits=True)
+    assert logits_rel_err(res["logits"], ref.logits) <= 2e-2
+    _check_rows(res, ref.logits)
+
+
 @pytest.mark.parametrize("shape,r,ctx_len", [(MID, 8, 2100), (MID, 5, 4090), (TINY, 4, 3000), (TINY, 3, 9000)],
                          ids=["mid-8-2100", "mid-5-4090", "tiny-4-3000", "tiny-3-9000"])
 def test_long_context_many_cuts(shape, r, ctx_len):
