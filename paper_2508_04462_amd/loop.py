@@ -37,34 +37,46 @@ def _loop_streams(device):
 
 class PlantedAgreement:
     """Benchmark / test stand-in for a trained draft (random-init models never agree with each
-    other): per text position the best-scored node of a level is made to carry the target's own
-    token with probability p as long as the best path has been right so far, and to hang below the
-    best node of the level above; everything else stays as the draft model produced it.  `truth`:
-    the target's own text, truth[i] = token of text index i.  Every text index has one draw, kept
-    for the whole run, so a level that is built again says the same thing."""
+    other).  For the new level of text position `index`, every node of the level above that carries
+    the target's own token of the position before gets, with probability p, the target's token of
+    this position as its best-scored child; otherwise, with probability q, as its second-best child
+    (a sibling that catches what the best path missed).  The best-scored node of the whole level is
+    made a child of the anchor (the best-scored node of the level above that still descends from
+    the token verified last), right or wrong by the same draw, so that the best path is the planted
+    one; everything else stays as the draft model produced it.  `truth`: the target's own text,
+    truth[i] = token of text index i.  Every text index has one draw of each kind, kept for the
+    whole run, so a level that is built again says the same thing."""
 
-    def __init__(self, truth: Sequence[int], p: float, seed: int, vocab: int):
+    def __init__(self, truth: Sequence[int], p: float, seed: int, vocab: int, q: float = 0.0):
         import numpy as np
 
-        self.truth, self.p, self.vocab = list(truth), p, vocab
+        self.truth, self.p, self.q, self.vocab = list(truth), p, q, vocab
         self.rng = np.random.default_rng(seed)
-        self.draw: Dict[int, float] = {}
-        self.ok: Dict[int, bool] = {}  # the best path is right up to and including this text index
+        self.draw: Dict[int, tuple] = {}
 
-    def restart(self, index: int) -> None:
-        """A new tree is rooted at text index `index`: its root is the target's own token."""
-        self.ok = {index: True}
-
-    def __call__(self, index: int, level: int, tokens: Sequence[int], parents: Sequence[int]):
+    def __call__(self, index: int, level: int, tokens: Sequence[int], parents: Sequence[int], anchor: int = 0,
+                 parent_tokens: Optional[Sequence[int]] = None):
         tokens, parents = list(tokens), list(parents)
-        known = index < len(self.truth)
+        known = 0 < index < len(self.truth)
         right = self.truth[index] if known else 0
+        wrong = (right + 1) % self.vocab
         if index not in self.draw:
-            self.draw[index] = float(self.rng.random())
-        good = self.ok.get(index - 1, True) and known and self.draw[index] < self.p
-        tokens[0] = right if good else (right + 1) % self.vocab
-        parents[0] = 0
-        self.ok[index] = good
+            self.draw[index] = (float(self.rng.random()), float(self.rng.random()))
+        first, second = self.draw[index][0] < self.p, self.draw[index][1] < self.q
+
+        def on_path(node):
+            return known and (parent_tokens is None or parent_tokens[node] == self.truth[index - 1])
+
+        parents[0] = anchor
+        tokens[0] = right if on_path(anchor) and first else wrong
+        for node in sorted(set(parents)):
+            if not on_path(node):
+                continue
+            kids = [e for e, pa in enumerate(parents) if pa == node]
+            if first:
+                tokens[kids[0]] = right
+            elif second and len(kids) > 1:
+                tokens[kids[1]] = right
         return tokens, parents
 
 
@@ -109,10 +121,12 @@ class ConcurrentLoop:
     1024 tree slots behind the draft's dense context are used up) does the draft start a new tree:
     it forwards the tokens committed since the last one as a chain in front of the new root.
 
-    plant(index, level, tokens, parents) -> (tokens, parents) lets a benchmark overwrite the draft's
-    proposals of one level for text position `index` (random-init models never agree, so a planted
-    acceptance rate stands in for the agreement of a trained draft with its target); None leaves
-    them as the draft made them."""
+    plant(index, level, tokens, parents, anchor, parent_tokens) -> (tokens, parents) lets a benchmark
+    overwrite the draft's proposals of one level for text position `index` (random-init models
+    never agree, so a planted acceptance rate stands in for the agreement of a trained draft with
+    its target); anchor: index, in the level above, of the best-scored node that descends from
+    the token verified last; parent_tokens: the tokens of the level above.  None leaves the
+    proposals as the draft made them."""
 
     def __init__(self, target: Target, draft: Target, ctx_len: int, pending: int, K: int = 32, k: int = 8, depth: int = 4,
                  plant: Optional[Callable] = None, wait_levels: int = 0, wait_ms: float = 20.0, r_max: Optional[int] = None,
@@ -240,8 +254,6 @@ class ConcurrentLoop:
             self.stats["stale_writes"] += 1
             return False
         self.stats["restarts"] += 1
-        if self.plant is not None and hasattr(self.plant, "restart"):
-            self.plant.restart(root_index)
         # mask rows of the chain [committed tokens ..., root]: each sees the one before it
         chain, prev_row = [], None
         for i in range(n_new + 1):
@@ -344,7 +356,8 @@ class ConcurrentLoop:
                 if cnt == 0:
                     raise RuntimeError("no extension below the verified token")
                 if self.plant is not None:
-                    nt, npar = self.plant(root_index + D + 1, D + 1, nt, npar)
+                    anchor = alive[D][0]  # the best-scored node of this level below the verified token
+                    nt, npar = self.plant(root_index + D + 1, D + 1, nt, npar, anchor, lv.tok)
                 if self.stop or self.cache.write(D + 1, nt, npar, ns, epoch=epoch) != B.CARD_OK:
                     self.stats["stale_writes"] += 1
                     continue  # the target has corrected the cache meanwhile: what was forwarded stays on record
