@@ -349,3 +349,30 @@ def test_argument_errors_of_the_later_entry_points_are_caught_on_the_host():
     assert card.card_cache_select(P, P, P, 0, 4, 8, P, P, P) == card.CARD_ERANGE
     assert card.card_cache_select(P, P, P, 200, 16, 8, P, P, P) == card.CARD_ERANGE  # more than 2048 tuples
     assert card.card_cache_select(P, None, P, 4, 4, 8, P, P, P) == card.CARD_EINVAL
+
+
+def test_planted_agreement_is_per_text_index_and_follows_every_on_path_parent():
+    """The benchmark's stand-in for a trained draft: one draw per text index (a level that is built
+    twice says the same thing), the target's token below every node that carries the target's
+    previous token, the best node of the level below the anchor, a sibling where the best misses."""
+    from paper_2508_04462_amd.loop import PlantedAgreement
+
+    truth = list(range(100, 140))
+    always = PlantedAgreement(truth, 1.0, 1, 1000)
+    toks, pars = always(5, 2, [7, 8, 9, 10], [1, 1, 2, 2], anchor=2, parent_tokens=[0, truth[4], truth[4]])
+    assert pars[0] == 2 and toks[0] == truth[5]          # best node: below the anchor, right
+    assert toks[1] == truth[5] and pars[1] == 1          # the other on-path parent gets its right child too
+    never = PlantedAgreement(truth, 0.0, 1, 1000)
+    toks, pars = never(5, 2, [7, 8, 9, 10], [1, 1, 2, 2], anchor=2, parent_tokens=[0, truth[4], truth[4]])
+    assert truth[5] not in toks and pars[0] == 2
+    sib = PlantedAgreement(truth, 0.0, 1, 1000, q=1.0)
+    toks, pars = sib(5, 2, [7, 8, 9, 10], [2, 2, 1, 1], anchor=2, parent_tokens=[0, truth[4], truth[4]])
+    assert toks[0] != truth[5] and toks[1] == truth[5] and toks[3] == truth[5] and toks[2] != truth[5]
+    # an anchor that is off the target's text gets nothing right
+    toks, _ = always(5, 2, [7, 8], [0, 0], anchor=0, parent_tokens=[55])
+    assert truth[5] not in toks
+    # the same index twice: the same decision
+    half = PlantedAgreement(truth, 0.5, 3, 1000)
+    first = [half(i, 1, [1, 2], [0, 0], 0, [truth[i - 1]])[0] for i in range(1, 30)]
+    again = [half(i, 1, [1, 2], [0, 0], 0, [truth[i - 1]])[0] for i in range(1, 30)]
+    assert first == again and 5 < sum(t[0] == truth[i] for i, t in zip(range(1, 30), first)) < 25
