@@ -392,6 +392,13 @@ int card_step_begin(card_cache* cache, const card_model_cfg* cfg, const void* pa
                     const card_kv* kv, int32_t ctx_len, int32_t max_len, int32_t* cand_staging,
                     void* workspace_dev, void* stream, card_verify_result* out,
                     int32_t* row_argmax_dev, card_step* step_host);
+/* card_step_begin at a sampling temperature (card_verify_sampled in place of card_verify: the
+ * loop then emits the text of token-by-token sampling with the same seed; the T = 1 columns of
+ * the main results).  row_token_dev receives the draws.  card_step_end is the same. */
+int card_step_begin_sampled(card_cache* cache, const card_model_cfg* cfg, const void* packed_weights_dev,
+                            const card_kv* kv, int32_t ctx_len, int32_t max_len, int32_t* cand_staging,
+                            void* workspace_dev, void* stream, card_verify_result* out,
+                            int32_t* row_token_dev, card_step* step_host, const card_sampling* sampling);
 int card_step_end(card_cache* cache, const card_step* step_host, const card_verify_result* out_host,
                   int32_t flags, int32_t* emitted_host, int32_t* n_emitted_host);
 

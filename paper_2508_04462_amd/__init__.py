@@ -38,6 +38,7 @@ from .binding import (  # noqa: F401
     card_cache_select,
     card_tree_mask_level,
     card_step_begin,
+    card_step_begin_sampled,
     card_step_end,
     card_verify_sampled,
     card_static_scratch_bytes,

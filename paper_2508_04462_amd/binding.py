@@ -103,6 +103,9 @@ def _declare(lib: C.CDLL) -> C.CDLL:
     lib.card_cache_select.argtypes = [_P, _P, _P, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P, _P]
     lib.card_step_begin.restype = C.c_int
     lib.card_step_begin.argtypes = [_P, _cfgp, _P, _kvp, C.c_int32, C.c_int32, _P, _P, _P, _P, _P, C.POINTER(CardStep)]
+    lib.card_step_begin_sampled.restype = C.c_int
+    lib.card_step_begin_sampled.argtypes = [_P, _cfgp, _P, _kvp, C.c_int32, C.c_int32, _P, _P, _P, _P, _P, C.POINTER(CardStep),
+                                            C.POINTER(CardSampling)]
     lib.card_step_end.restype = C.c_int
     lib.card_step_end.argtypes = [_P, C.POINTER(CardStep), _P, C.c_int32, _i32p, _i32p]
     lib.card_verify_static.restype = C.c_int
@@ -235,6 +238,13 @@ def card_step_begin(cache, cfg, packed_dev, kv: CardKV, ctx_len: int, max_len: i
     return lib.card_step_begin(cache, C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, max_len,
                                _ptr(cand_staging), _ptr(workspace_dev), _ptr(stream), _ptr(out),
                                _ptr(row_argmax_dev), C.byref(step))
+
+
+def card_step_begin_sampled(cache, cfg, packed_dev, kv: CardKV, ctx_len: int, max_len: int, cand_staging, workspace_dev,
+                            stream, out, row_token_dev, step: CardStep, sampling: CardSampling) -> int:
+    return lib.card_step_begin_sampled(cache, C.byref(cfg), _ptr(packed_dev), C.byref(kv), ctx_len, max_len,
+                                       _ptr(cand_staging), _ptr(workspace_dev), _ptr(stream), _ptr(out),
+                                       _ptr(row_token_dev), C.byref(step), C.byref(sampling))
 
 
 def card_step_end(cache, step: CardStep, out_host, flags: int = 0):

@@ -431,9 +431,9 @@ int card_cache_select(const float* sigma_dev, const int32_t* topk_tokens_dev, co
     return st != CARD_OK ? st : (K < n_parents * k ? K : n_parents * k);
 }
 
-int card_step_begin(card_cache* cache, const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
+static int step_begin_impl(card_cache* cache, const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
                     int32_t ctx_len, int32_t max_len, int32_t* cand_staging, void* workspace_dev, void* stream,
-                    card_verify_result* out, int32_t* row_argmax_dev, card_step* step_host) {
+                    card_verify_result* out, int32_t* row_argmax_dev, card_step* step_host, const card_sampling* sampling) {
     if (!cache || !cfg || !kv || !cand_staging || !step_host) return CARD_EINVAL;
     if (max_len < 1 || max_len > cfg->max_r || max_len > kMaxR) return CARD_ERANGE;
     if (kv->pending_token < 0) return CARD_EINVAL;  // the query key is the token just verified
@@ -450,7 +450,24 @@ int card_step_begin(card_cache* cache, const card_model_cfg* cfg, const void* pa
     step_host->path_score = hit > 0 ? score : 0.f;
     for (int i = 0; i < n; ++i) cand_staging[i] = step_host->cand[i];
     return verify_impl(cfg, packed_weights_dev, kv, ctx_len, cand_staging, n, workspace_dev, stream, out, row_argmax_dev,
-                       nullptr);
+                       nullptr, sampling);
+}
+
+
+int card_step_begin(card_cache* cache, const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
+                    int32_t ctx_len, int32_t max_len, int32_t* cand_staging, void* workspace_dev, void* stream,
+                    card_verify_result* out, int32_t* row_argmax_dev, card_step* step_host) {
+    return step_begin_impl(cache, cfg, packed_weights_dev, kv, ctx_len, max_len, cand_staging, workspace_dev, stream, out,
+                           row_argmax_dev, step_host, nullptr);
+}
+
+int card_step_begin_sampled(card_cache* cache, const card_model_cfg* cfg, const void* packed_weights_dev, const card_kv* kv,
+                    int32_t ctx_len, int32_t max_len, int32_t* cand_staging, void* workspace_dev, void* stream,
+                    card_verify_result* out, int32_t* row_argmax_dev, card_step* step_host,
+                            const card_sampling* sampling) {
+    if (!sampling || !(sampling->temperature >= 0.f)) return CARD_EINVAL;
+    return step_begin_impl(cache, cfg, packed_weights_dev, kv, ctx_len, max_len, cand_staging, workspace_dev, stream, out,
+                           row_argmax_dev, step_host, sampling);
 }
 
 int card_step_end(card_cache* cache, const card_step* step_host, const card_verify_result* out_host, int32_t flags,

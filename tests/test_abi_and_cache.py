@@ -232,6 +232,10 @@ def test_step_begin_argument_errors():
     no_pending = card.CardKV(0x1000, 0x1000, 0x1000, 16, -1)
     assert card.card_step_begin(c.h, cfg, 0x1000, no_pending, 0, 4, 0x1000, 0x1000, None, 0x1000, None, step) == card.CARD_EINVAL
     assert card.card_step_begin(None, cfg, 0x1000, kv, 0, 4, 0x1000, 0x1000, None, 0x1000, None, step) == card.CARD_EINVAL
+    smp = card.CardSampling(1.0, 7)
+    assert card.card_step_begin_sampled(c.h, cfg, 0x1000, kv, 0, 0, 0x1000, 0x1000, None, 0x1000, None, step, smp) == card.CARD_ERANGE
+    assert card.card_step_begin_sampled(c.h, cfg, 0x1000, kv, 0, 4, 0x1000, 0x1000, None, 0x1000, None, step,
+                                        card.CardSampling(-2.0, 7)) == card.CARD_EINVAL
 
 
 def test_tree_mask_level_matches_the_mask_oracle():

@@ -177,6 +177,53 @@ def test_step_calls_variable_paths_miss_fallback_and_the_no_correct_variant(flag
         assert cache.depth() >= 1
 
 
+def test_step_calls_at_a_sampling_temperature_emit_the_sampled_text():
+    """card_step_begin_sampled: the same loop with the target sampling from the seeded generator
+    emits exactly what token-by-token sampling with that seed emits (the text the draft is scripted
+    after), with hits, misses and ragged paths on the way."""
+    import torch
+
+    import paper_2508_04462_amd as card
+
+    shape, n_new, r, seed, T, sseed = TINY, 24, 6, 8, 1.0, 4242
+    tgt, _ = make_pair(shape, seed, max_ctx=shape.ctx + n_new + r + 24)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, shape.ctx, shape.vocab).tolist()
+    tgt.prefill(ctx[:-1])
+    g0 = tgt.verify(shape.ctx - 1, -1, [ctx[-1]], temperature=T, seed=sseed)["row_argmax"][0]
+    truth, pos = [g0], shape.ctx
+    for _ in range(n_new + r):
+        truth.append(tgt.verify(pos, truth[-1], [truth[-1]], temperature=T, seed=sseed)["correction_token"])
+        pos += 1
+    cache = card.CandidateCache(K=8, max_depth=r)
+    rng = np.random.default_rng(seed)
+    staging = torch.zeros(32, dtype=torch.int32).pin_memory()
+    out = torch.zeros(4, dtype=torch.int32).pin_memory()
+    step, sampling = card.CardStep(), card.CardSampling(T, sseed)
+    n, pending, emitted, hits, it = shape.ctx, g0, [g0], 0, 0
+    while len(emitted) < n_new:
+        e = len(emitted) - 1
+        if it % 2 == 0:
+            _draft(cache, truth[e:] + [0] * r, rng, 0.8, 2 + it % (r - 1), 4)
+        it += 1
+        st = card.card_step_begin_sampled(cache.h, tgt.cfg, tgt.packed, tgt.kv(pending), n, r, staging, tgt.workspace,
+                                          tgt._stream(), out, tgt.row_argmax, step, sampling)
+        assert st == card.CARD_OK, card.card_strerror(st)
+        torch.cuda.current_stream().synchronize()
+        hits += step.hit
+        acc, corr, first, count = out.tolist()
+        assert 1 <= acc <= step.r and (first, count) == (n, acc)
+        st, toks = card.card_step_end(cache.h, step, out, 0)
+        assert st == card.CARD_OK and toks == list(step.cand[1:acc]) + [corr]
+        emitted += toks
+        n += acc
+        pending = corr
+    assert emitted == truth[: len(emitted)]
+    assert hits >= 2 and len(emitted) > it  # some steps emitted more than one token
+    bad = card.CardSampling(-1.0, 0)
+    assert card.card_step_begin_sampled(cache.h, tgt.cfg, tgt.packed, tgt.kv(pending), n, r, staging, tgt.workspace,
+                                        tgt._stream(), out, tgt.row_argmax, step, bad) == card.CARD_EINVAL
+
+
 @pytest.mark.parametrize("p,seed,grids", [(0.7, 11, (128, 64)), (0.95, 42, (192, 64)), (0.0, 27, (64, 32))],
                          ids=["p0.7", "p0.95", "p0"])
 def test_concurrent_draft_and_target_on_one_gpu_is_lossless(p, seed, grids):
