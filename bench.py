@@ -376,7 +376,7 @@ def concurrent_loop_entries(args, decode_tps, quick):
     return out
 
 
-def draft_level_entry(args, quick, probe_levels=0):
+def draft_level_entry(args, quick, probe_levels=0, lanes=1):
     """The draft side of cache construction (Cache Construction, eqs. (1)-(9)) as one sweep entry: a
     1B-shaped draft on the whole GPU builds cache levels of K = 100 nodes, top-8 per node, below a
     root behind 1024 tokens of context.  A level is forwarded in ceil(K / 32) calls of the
@@ -394,8 +394,13 @@ def draft_level_entry(args, quick, probe_levels=0):
     shape = ci.ModelShape("tiny-draft", 1, 128, 2, 1, 64, 344, 1024) if quick else ci.SHAPES["llama1b"]
     ctx_len, K, k = (64, 40, 4) if quick else (1024, 100, 8)
     n_levels = probe_levels if probe_levels else (2 if quick else 4)
-    dr = card.Target(shape, ctx_len + 16 + K * (n_levels + 1) + 64, max_r=32)
+    grid = 0
+    if lanes > 1:  # the calls of a level side by side, each on its share of the compute units
+        grid = torch.cuda.get_device_properties(0).multi_processor_count // lanes // 8 * 8
+    dr = card.Target(shape, ctx_len + 16 + K * (n_levels + 1) + 64, max_r=32, grid_wgs=grid)
     load_synthetic_weights(dr, shape, args.seed + 100)
+    if lanes > 1:
+        dr.enable_lanes(lanes)
     dev = dr.device
     root = dr.prefill(ci.uniform_tokens(args.seed, "ctx_tokens", 0, ctx_len, shape.vocab).tolist())
     mask_base = ctx_len // 16 * 16
@@ -410,11 +415,16 @@ def draft_level_entry(args, quick, probe_levels=0):
         tk = torch.empty((n, k), dtype=torch.int32, device=dev)
         tp = torch.empty((n, k), dtype=torch.float32, device=dev)
         calls = 0
-        for c0 in range(0, n, 32):
-            c1 = min(n, c0 + 32)
-            res = dr.draft_level(ctx_len, tokens[c0:c1], [position] * (c1 - c0), first + c0, rows[c0:c1], mask_base, k)
-            tk[c0:c1], tp[c0:c1] = res["topk_tokens"], res["topk_probs"]
-            calls += 1
+        if lanes > 1 and n > 1:
+            res = dr.draft_level_wide(ctx_len, tokens, [position] * n, first, rows, mask_base, k)
+            tk, tp = res["topk_tokens"], res["topk_probs"]
+            calls = (n + 31) // 32
+        else:
+            for c0 in range(0, n, 32):
+                c1 = min(n, c0 + 32)
+                res = dr.draft_level(ctx_len, tokens[c0:c1], [position] * (c1 - c0), first + c0, rows[c0:c1], mask_base, k)
+                tk[c0:c1], tp[c0:c1] = res["topk_tokens"], res["topk_probs"]
+                calls += 1
         ot = torch.empty(K, dtype=torch.int32, device=dev)
         os_ = torch.empty(K, dtype=torch.float32, device=dev)
         op = torch.empty(K, dtype=torch.int32, device=dev)
@@ -445,6 +455,7 @@ def draft_level_entry(args, quick, probe_levels=0):
     params = shape.streamed_weight_bytes() // 2
     rows_issued = 32 * (n_nodes // 32) + (0 if n_nodes % 32 == 0 else (8 if n_nodes % 32 <= 8 else 16 if n_nodes % 32 <= 16 else 32))
     return {"kind": "draft_level", "draft": shape.name, "ctx": ctx_len, "K": n_nodes, "k": k, "calls_per_level": calls,
+            "calls_side_by_side": lanes, "workgroups_per_call": grid if grid else "all compute units",
             "ms_per_level": ms, "ms_per_call": ms / calls, "nodes_per_s": n_nodes / (ms * 1e-3),
             "hbm_frac": calls * (shape.streamed_weight_bytes() + shape.kv_bytes(ctx_len)) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             # matrix-pipe work issued: two instructions (high and low activation halves) per weight
@@ -489,6 +500,7 @@ def run_sweep(args, rig8b):
         section("cache loop", lambda: out.append(cache_loop(rig8b, 8, 0.6, 16)))
         section("concurrent loop", lambda: out.extend(concurrent_loop_entries(args, state["decode_tps"], True)))
         section("draft level", lambda: out.append(draft_level_entry(args, True)))
+        section("draft level, two calls side by side", lambda: out.append(draft_level_entry(args, True, lanes=2)))
         return out
     rig8b.close()
 
@@ -529,6 +541,7 @@ def run_sweep(args, rig8b):
     section("llama70b r sweep", llama70b)
     section("concurrent loop", lambda: out.extend(concurrent_loop_entries(args, state["decode_tps"], False)))
     section("draft level", lambda: out.append(draft_level_entry(args, False)))
+    section("draft level, two calls side by side", lambda: out.append(draft_level_entry(args, False, lanes=2)))
     return out
 
 

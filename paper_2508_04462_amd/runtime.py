@@ -15,6 +15,18 @@ def make_cfg(shape, max_ctx: int, max_r: int = 32, grid_wgs: int = 0) -> B.CardM
                           shape.d_ffn, shape.vocab, shape.rope_theta, shape.rms_eps, 16, max_ctx, max_r, grid_wgs)
 
 
+_LANE_STREAMS: Dict[str, list] = {}
+
+
+def _lane_streams(device, lanes: int) -> list:
+    """Streams for calls that are to run side by side, created once per device: a process has few
+    hardware queues and streams are mapped onto them in turn."""
+    have = _LANE_STREAMS.setdefault(str(device), [])
+    while len(have) < lanes:
+        have.append(torch.cuda.Stream(device=device))
+    return have[:lanes]
+
+
 def _check(st: int, where: str) -> None:
     if st != B.CARD_OK:
         raise B.CardError(st, where)
@@ -121,6 +133,62 @@ class Target:
         if want_logits:
             res["logits"] = logits.cpu()
         return res
+
+    # -- a level wider than one call: several calls side by side
+    def enable_lanes(self, lanes: int) -> None:
+        """Prepare `lanes` workspaces and streams for draft_level_wide.  The model must have been
+        created with grid_wgs set so that lanes * grid_wgs workgroups fit the GPU: every call of a
+        level then runs on its own share of the compute units."""
+        cus = torch.cuda.get_device_properties(self.device).multi_processor_count
+        if self.cfg.grid_wgs <= 0 or lanes * self.cfg.grid_wgs > cus:
+            raise ValueError("lanes * grid_wgs must fit the compute units")
+        self._lane_ws = [self.workspace]
+        for _ in range(lanes - 1):
+            ws = torch.empty_like(self.workspace)
+            _check(B.card_workspace_init(self.cfg, ws, self._stream()), "card_workspace_init")
+            self._lane_ws.append(ws)
+        self._lane_streams = _lane_streams(self.device, lanes)
+        torch.cuda.current_stream(self.device).synchronize()
+
+    def draft_level_wide(self, ctx_len: int, tokens: Sequence[int], positions: Sequence[int], first_slot: int,
+                         mask_rows: Sequence[Sequence[int]], mask_base: int, k: int) -> Dict:
+        """card_draft_level for a level of any width: the rows are cut into calls of at most 32, `lanes`
+        of them at a time enqueued side by side, each on its own stream with its own workspace
+        (peers of a level never see each other, so the calls are independent; they share the weights
+        and the KV cache and write different slots; a lane's calls follow each other on its stream).
+        Same results as the calls one after the other."""
+        n, words, dev = len(tokens), len(mask_rows[0]), self.device
+        lanes = len(self._lane_ws)
+        tok = torch.tensor([int(t) for t in tokens], dtype=torch.int32, device=dev)
+        pos = torch.tensor([int(p) for p in positions], dtype=torch.int32, device=dev)
+        mask = torch.tensor([[int(w) - (1 << 32) if int(w) >= (1 << 31) else int(w) for w in row] for row in mask_rows],
+                            dtype=torch.int32, device=dev)
+        tk = torch.full((n, k), -7, dtype=torch.int32, device=dev)
+        tp = torch.zeros((n, k), dtype=torch.float32, device=dev)
+        cur = torch.cuda.current_stream(dev)
+        ready = torch.cuda.Event()
+        ready.record(cur)
+        calls = (n + 31) // 32
+        calls = (calls + lanes - 1) // lanes * lanes  # full rounds of side-by-side calls, rows spread evenly
+        per = min(32, ((n + calls - 1) // calls + 7) // 8 * 8)  # whole 8-row groups per call where the level allows
+        done = []
+        for i, c0 in enumerate(range(0, n, per)):
+            c1 = min(n, c0 + per)
+            lane = i % lanes
+            st = self._lane_streams[lane]
+            if i < lanes:
+                st.wait_event(ready)
+            rows = B.CardTreeRows(tok[c0:c1].data_ptr(), pos[c0:c1].data_ptr(), int(first_slot) + c0, mask[c0:c1].data_ptr(),
+                                  words, int(mask_base))
+            _check(B.card_draft_level(self.cfg, self.packed, self.kv(-1), ctx_len, rows, c1 - c0, k, self._lane_ws[lane],
+                                      st.cuda_stream, tk[c0:c1], tp[c0:c1], None), "card_draft_level")
+            ev = torch.cuda.Event()
+            ev.record(st)
+            done.append(ev)
+        for ev in done:
+            cur.wait_event(ev)
+        cur.synchronize()
+        return {"topk_tokens": tk, "topk_probs": tp}
 
     def prefill(self, tokens: Sequence[int], chunk: int = 32) -> int:
         """Build KV[0:n) with verify calls that carry no pending token; returns the arg-max after

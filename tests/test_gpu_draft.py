@@ -200,3 +200,41 @@ def test_three_levels_built_on_the_device_and_written_to_the_cache():
     assert cache.depth() == depth + 1
     hit, path, score = cache.query(g0, depth + 1)
     assert hit and path[0] == g0 and len(path) == depth + 1
+
+
+def test_a_wide_level_in_calls_side_by_side_equals_the_calls_one_after_the_other():
+    """A level of 100 nodes on four lanes (each call on its own 64 workgroups, workspace and
+    stream) gives bit for bit what four calls in a row on the same grid give, and leaves the same
+    keys in the cache."""
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape, seed, ctx_len, n, k = MID, 21, 70, 100, 8
+    tgt = card.Target(shape, 320, max_r=32, grid_wgs=64)
+    load_synthetic_weights(tgt, shape, seed, 0.2)
+    tgt.enable_lanes(4)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, ctx_len, shape.vocab).tolist()
+    tgt.prefill(ctx)
+    rng = np.random.default_rng(seed)
+    mask_base, first = ctx_len // 16 * 16, 80
+    words = (first + 1 + 2 * n - mask_base + 31) // 32
+    st, root_row = card.card_tree_mask_level(None, [-1], first, ctx_len, mask_base, words)
+    tgt.draft_level(ctx_len, [5], [ctx_len], first, root_row, mask_base, k)
+    toks = rng.integers(0, shape.vocab, size=n).tolist()
+    out = {}
+    for name, base in (("row", first + 1), ("wide", first + 1)):  # the same slots: the same sums in the same order
+        st, rows = card.card_tree_mask_level(root_row, [0] * n, base, ctx_len, mask_base, words)
+        assert st == card.CARD_OK
+        if name == "wide":
+            res = tgt.draft_level_wide(ctx_len, toks, [ctx_len + 1] * n, base, rows, mask_base, k)
+            tk, tp = res["topk_tokens"].cpu(), res["topk_probs"].cpu()
+        else:
+            parts = [tgt.draft_level(ctx_len, toks[c:c + 32], [ctx_len + 1] * len(toks[c:c + 32]), base + c, rows[c:c + 32],
+                                     mask_base, k) for c in range(0, n, 32)]
+            tk = torch.cat([p["topk_tokens"].cpu() for p in parts])
+            tp = torch.cat([p["topk_probs"].cpu() for p in parts])
+        kk, vv = tgt.kv_gather(shape.n_layers - 1, base, n)
+        out[name] = (tk, tp, kk, vv)
+    for a, b in zip(out["row"], out["wide"]):
+        assert torch.equal(a, b)
+    assert (out["wide"][0] >= 0).all()

@@ -51,7 +51,8 @@ def test_short_run_prints_one_json_line_with_the_contract_fields(monkeypatch, ca
     assert conc and all("error" in e or (e["text_equals_plain_decode"] and e["accepted_tokens_per_s"] > 0) for e in conc)
     pts = [e for e in pts if e.get("kind") != "concurrent_loop"]
     dl = [e for e in sw if e.get("kind") == "draft_level"]
-    assert len(dl) == 1 and dl[0]["ms_per_level"] > 0 and dl[0]["calls_per_level"] == (dl[0]["K"] + 31) // 32
+    assert len(dl) == 2 and all(e["ms_per_level"] > 0 and e["calls_per_level"] == (e["K"] + 31) // 32 for e in dl)
+    assert sorted(e["calls_side_by_side"] for e in dl) == [1, 2]
     loops = [e for e in sw if e.get("kind") == "cache_loop"]
     assert loops and all("error" in e or (e["accepted_tokens_per_s"] > 0 and 1.0 <= e["mean_accepted_len"] <= e["r"])
                          for e in loops)
