@@ -293,7 +293,7 @@ def cache_loop(rig, r, p, n_tokens, K=50, width=10):
             "plain_decode_tokens_per_s": None}
 
 
-def concurrent_loop_entries(args, decode_tps, quick):
+def concurrent_loop_entries(args, decode_tps, quick, grids=(192, 64)):
     """Draft and target running at the same time on one GPU (two host threads, two streams, the
     compute units split between the two persistent kernels): the paper's own pairing, a 70B-shaped
     target (on 192 workgroups) with a 1B-shaped draft (on 64), context 1024, K = 8 nodes per
@@ -309,7 +309,6 @@ def concurrent_loop_entries(args, decode_tps, quick):
     t_shape = ci.SHAPES["tiny" if quick else "llama70b"]
     d_shape = ci.ModelShape("tiny-draft", 1, 128, 2, 1, 64, 344, 1024) if quick else ci.SHAPES["llama1b"]
     ctx_len, n_tok = (128, 24) if quick else (1024, 64)
-    grids = (192, 64)
     depth, r_max = (3, 4) if quick else (12, 8)
     runs = ((0.6, 0.0),) if quick else ((0.3, 0.0), (0.6, 0.0), (0.9, 0.0), (0.6, 0.6))
     n_text = len(runs) * (n_tok + 60) + 24  # room to step over positions where the target's two best tokens nearly tie
