@@ -48,6 +48,8 @@ def parse():
                     help="full: every synthetic configuration; quick: one point per kind on the headline shape; none")
     ap.add_argument("--draft-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: three cache levels of K = 100 nodes on the 1B-shaped draft, no timing")
+    ap.add_argument("--loop-probe", action="store_true",
+                    help="for rocprofv3 --kernel-trace runs: the concurrent draft/target loop alone (70B + 1B shapes)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a 1 GiB device copy (calibration) and 5 verify steps, no timing")
     return ap.parse_args()
@@ -560,6 +562,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.loop_probe:
+        print(json.dumps(concurrent_loop_entries(args, None, False)))
+        return
     if args.draft_probe:
         print(json.dumps(draft_level_entry(args, False, probe_levels=3)))
         return
