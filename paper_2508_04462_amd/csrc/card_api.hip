@@ -206,12 +206,16 @@ int verify_impl(const card_model_cfg* cfg, const void* packed, const card_kv* kv
     // Cut the context so that a workgroup's share fits the page buffers of its wavefronts (all of
     // its old-context pages are then in flight before the barrier in front of attention), as long
     // as every task still gets a workgroup of its own; beyond that the shares grow instead.
+    // The cut length is a function of the context length in steps of 512 tokens, the grid and
+    // the kernel (r <= 8, <= 16, <= 32), not of r itself: a row's keys are then cut, summed and
+    // merged in the same order whether a step of eight rows or a plain decode step computes it,
+    // and verification reproduces the plain decode's logits bit for bit (same kernel, same
+    // 512-token stretch).
     const int share = kMegaWaves * (h == 128 ? 2 : 4);
-    int splits = ceil_div(a.pages_used, share);
-    const int max_by_grid = std::max(1, cus / (a.Hkv * a.row_tiles));
-    if (splits > max_by_grid) splits = max_by_grid;
-    if (splits > L.m_attn_max_splits) splits = L.m_attn_max_splits;
-    a.pages_per_split = ceil_div(a.pages_used, splits);
+    const int r_kernel = r <= 8 ? 8 : (r <= 16 ? 16 : 32);
+    const int max_cuts = std::min<int>(L.m_attn_max_splits, std::max(1, cus / (a.Hkv * ceil_div(a.G * r_kernel, 16))));
+    const int pages_stretch = ceil_div(a.pages_used, 32) * 32;
+    a.pages_per_split = std::max(share, ceil_div(pages_stretch, max_cuts));
     a.a_splits = ceil_div(a.pages_used, a.pages_per_split);
     a.xres = reinterpret_cast<float*>(ws + L.m_xres_off);
     a.xfrag = reinterpret_cast<__bf16*>(ws + L.m_xfrag_off);

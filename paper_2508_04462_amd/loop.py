@@ -18,21 +18,15 @@ from typing import Callable, Dict, List, Optional, Sequence
 import torch
 
 from . import binding as B
-from .runtime import CandidateCache, Target
-
-
-_STREAMS: Dict[str, tuple] = {}
+from .runtime import CandidateCache, Target, _lane_streams
 
 
 def _loop_streams(device):
-    """One pair of streams per device for the life of the process.  A process has few hardware queues
-    (four by default) and streams are mapped onto them in turn: fresh streams for every loop end up
-    sharing a queue sooner or later, and the two kernels then run one after the other, not side by
-    side."""
-    key = str(device)
-    if key not in _STREAMS:
-        _STREAMS[key] = (torch.cuda.Stream(device=device), torch.cuda.Stream(device=device))
-    return _STREAMS[key]
+    """The two streams of the loop: the process-wide pool of side-by-side streams (a process has few
+    hardware queues, four by default, and streams are mapped onto them in turn: more streams than
+    that end up sharing a queue, and two kernels on one queue run one after the other)."""
+    a, b = _lane_streams(device, 2)
+    return a, b
 
 
 class PlantedAgreement:

@@ -19,8 +19,10 @@ _LANE_STREAMS: Dict[str, list] = {}
 
 
 def _lane_streams(device, lanes: int) -> list:
-    """Streams for calls that are to run side by side, created once per device: a process has few
-    hardware queues and streams are mapped onto them in turn."""
+    """Streams for kernels that are to run side by side, created once per device and shared by
+    everything that needs such streams: a process has few hardware queues (four by default) and
+    streams are mapped onto them in turn, so every further stream risks sharing a queue with
+    another one, and two kernels on one queue run one after the other."""
     have = _LANE_STREAMS.setdefault(str(device), [])
     while len(have) < lanes:
         have.append(torch.cuda.Stream(device=device))

@@ -323,3 +323,34 @@ def test_distance_to_the_textbook_decoder_with_an_unrounded_cache(shape, ctx_len
         print(f"\n[{shape.name}] logits vs oracle with bf16 cache {e_bf16:.2e}, vs unrounded cache {e_exact:.2e}")
     assert e_bf16 <= bound and e_exact <= bound
     assert e_bf16 <= e_exact  # the cache precision the path implements is the closer one
+
+
+@pytest.mark.parametrize("shape,ctx_len,grid", [(MID, 200, 0), (MID, 333, 192), (TINY, 700, 0), (MID, 1290, 64)],
+                         ids=["mid", "mid-192", "tiny-long", "mid-64"])
+def test_a_verified_row_has_the_plain_decode_step_logits_bit_for_bit(shape, ctx_len, grid):
+    """Losslessness in the strongest form: the logits of row i of an r-row step (r <= 8) equal,
+    bit for bit, those of the plain decode step at the same position - same products, same order
+    of every sum (the attention cuts depend on the context length in steps of 512 tokens, not on r).
+    So the accepted prefix can never depend on how the text is cut into steps."""
+    import paper_2508_04462_amd as card
+    from gpu_common import shuffled_pages
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    seed = 17
+    max_ctx = (ctx_len + 40 + 15) // 16 * 16
+    tgt = card.Target(shape, max_ctx, page_order=shuffled_pages(max_ctx // 16, seed), grid_wgs=grid)
+    load_synthetic_weights(tgt, shape, seed, 0.2)
+    toks = ci.uniform_tokens(seed, "ctx_tokens", 0, ctx_len + 8, shape.vocab).tolist()
+    tgt.prefill(toks[:ctx_len])
+    plain = []
+    for i in range(8):  # plain decode over the eight tokens, one row per step
+        res = tgt.verify(ctx_len + i, -1, [toks[ctx_len + i]], want_logits=True)
+        plain.append(res["logits"][0].clone())
+    for r in (8, 5, 2):
+        res = tgt.verify(ctx_len, -1, toks[ctx_len:ctx_len + r], want_logits=True)
+        for i in range(r):
+            assert torch.equal(res["logits"][i], plain[i]), (r, i, float((res["logits"][i] - plain[i]).abs().max()))
+    # and a step that starts in the middle
+    res = tgt.verify(ctx_len + 3, -1, toks[ctx_len + 3:ctx_len + 8], want_logits=True)
+    for i in range(5):
+        assert torch.equal(res["logits"][i], plain[3 + i]), i
