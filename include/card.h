@@ -148,7 +148,11 @@ typedef struct card_verify_result {
  * ctx_len .. ctx_len+r-1 against kv[0, ctx_len), causal among themselves; writes K and V of
  * all r rows into the cache; candidate i is accepted iff every earlier one was and it equals
  * pred[i], where pred[0] = kv->pending_token and pred[i] = arg-max (lowest index on ties) of
- * row i-1's vocabulary logits.  Logits are never written to memory.
+ * row i-1's vocabulary logits.  Logits are never written to memory.  Every sum of the step is
+ * taken per row in an order that does not depend on r (within r <= 8, r <= 16 and r <= 32 each,
+ * on one grid, as long as ctx_len + r stays inside the same stretch of 512 tokens): row i of a
+ * step has bit for bit the logits of the plain decode step (r = 1) at its position, so what is
+ * accepted never depends on how the text is cut into steps.
  *   packed_weights_dev : blob filled by card_weights_pack_tensor
  *   kv                 : host struct (read during the call only)
  *   cand_tokens_dev    : dev (or device-visible pinned host memory, as card_step_begin uses:
