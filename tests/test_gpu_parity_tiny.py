@@ -354,3 +354,9 @@ def test_a_verified_row_has_the_plain_decode_step_logits_bit_for_bit(shape, ctx_
     res = tgt.verify(ctx_len + 3, -1, toks[ctx_len + 3:ctx_len + 8], want_logits=True)
     for i in range(5):
         assert torch.equal(res["logits"][i], plain[3 + i]), i
+    # the same holds inside the other two kernels: rows of a shorter step are rows of a longer one
+    more = ci.uniform_tokens(seed, "cand_tokens", 0, 32, shape.vocab).tolist()
+    for r_short, r_long in ((10, 16), (20, 32)):
+        a = tgt.verify(ctx_len, -1, more[:r_long], want_logits=True)["logits"]
+        b = tgt.verify(ctx_len, -1, more[:r_short], want_logits=True)["logits"]
+        assert torch.equal(a[:r_short], b), (r_short, r_long)
