@@ -79,6 +79,12 @@ def _run(golden_name, logit_tol=LOGIT_TOL):
         assert np.all(np.abs(np.abs(full).max(axis=1) - np.asarray(case["row_absmax"])) / np.asarray(case["row_absmax"])
                       <= logit_tol)
     assert checked_rows > 0
+    # at full size too, a verified row has the plain decode step's logits bit for bit
+    cand = g["cases"][-1]["cand"]
+    step = tgt.verify(ctx_len, g0, cand, want_logits=True)["logits"]
+    for i in range(min(3, r)):
+        one = tgt.verify(ctx_len + i, -1, [cand[i]], want_logits=True)["logits"][0]
+        assert torch.equal(step[i], one), i
     _window_case(tgt, g, ctx, logit_tol)
     return g
 
