@@ -144,7 +144,6 @@ class ConcurrentLoop:
         self.committed: List[int] = []  # tokens the target has committed behind the prompt
         self.corrections: List[List[int]] = []  # the token lists of the target's corrections, in order
         self.emitted: List[int] = [int(pending)]
-        self.ctx0 = ctx_len
         self.d_ctx = ctx_len          # draft: dense context length (prompt + absorbed tokens)
         self.d_absorbed = 0           # committed tokens that are part of the draft's dense context
         self.d_corr_seen = 0
