@@ -204,3 +204,49 @@ def test_draft_tree_forward_at_full_depth(golden_name):
     print(f"[{golden_name}] worst sampled logit error {worst:.2e} of the row maximum; {sets} rows with a decisive top-{k} set, "
           f"{orders} decisive ranks; g0 {'equal' if g0 == g['g0'] else 'differs (near tie)'}")
     assert sets >= 8 and orders >= 40
+
+
+@pytest.mark.parametrize("ctx_len", [8200, 32700])
+def test_long_contexts_at_full_size_hold_what_holds_at_any_size(ctx_len):
+    """8B shape at contexts the host oracle cannot reach in reasonable time (many cuts, page-buffer
+    refills inside a cut): properties that hold at any size.  (1) A row of an eight-row step has
+    the plain decode step's logits bit for bit.  (2) Where the pages lie in the pool does not
+    matter: after moving every page to another place (and saying so in the block table) the step
+    gives the same bits.  (3) The keys a step stores are the ones a plain decode step stores.
+    The cache holds noise for the context (no prefill of 32k tokens needed for any of this)."""
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape, seed, r = ci.SHAPES["llama8b"], 4, 8
+    max_ctx = (ctx_len + 64 + 15) // 16 * 16
+    n_pages = max_ctx // 16
+    tgt = card.Target(shape, max_ctx, page_order=shuffled_pages(n_pages, seed))
+    load_synthetic_weights(tgt, shape, seed)
+    gen = torch.Generator(device=tgt.device)
+    gen.manual_seed(seed)
+    for pool in (tgt.k_pages, tgt.v_pages):
+        v = pool.view(torch.bfloat16)
+        for i in range(0, v.numel(), 1 << 28):
+            v[i:i + (1 << 28)].normal_(0.0, 0.5, generator=gen)
+    toks = ci.uniform_tokens(seed, "cand_tokens", 0, r, shape.vocab).tolist()
+    plain, keys = [], []
+    for i in range(r):
+        plain.append(tgt.verify(ctx_len + i, -1, [toks[i]], want_logits=True)["logits"][0].clone())
+    k_plain, v_plain = tgt.kv_gather(shape.n_layers - 1, ctx_len, r)
+    step = tgt.verify(ctx_len, -1, toks, want_logits=True)["logits"].clone()
+    for i in range(r):
+        assert torch.equal(step[i], plain[i]), i
+    k_step, v_step = tgt.kv_gather(shape.n_layers - 1, ctx_len, r)
+    assert torch.equal(k_step, k_plain) and torch.equal(v_step, v_plain)
+    # move the pages: new place of logical page j = perm[old place]
+    old = tgt.block_table.cpu()
+    perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(seed + 1))
+    per_layer = tgt.k_pages.numel() // shape.n_layers
+    for pool in (tgt.k_pages, tgt.v_pages):
+        view = pool.view(shape.n_layers, n_pages, per_layer // n_pages)
+        moved = torch.empty_like(view)
+        moved[:, perm.to(tgt.device)] = view
+        view.copy_(moved)
+    tgt.block_table.copy_(perm[old.long()].to(torch.int32))
+    again = tgt.verify(ctx_len, -1, toks, want_logits=True)["logits"]
+    assert torch.equal(again, step)
