@@ -360,3 +360,26 @@ def test_a_verified_row_has_the_plain_decode_step_logits_bit_for_bit(shape, ctx_
         a = tgt.verify(ctx_len, -1, more[:r_long], want_logits=True)["logits"]
         b = tgt.verify(ctx_len, -1, more[:r_short], want_logits=True)["logits"]
         assert torch.equal(a[:r_short], b), (r_short, r_long)
+
+
+def test_the_grid_size_changes_no_bit_at_r_up_to_eight():
+    """Which workgroup owns a tile does not enter the arithmetic (the four wavefronts of the owner
+    cut K the same way, wherever the owner sits), and at short contexts the attention cuts do not
+    depend on the grid either: a model on 192 or 64 workgroups - the target or the draft of the
+    concurrent loop - computes bit for bit what it computes on the whole GPU."""
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape, seed, ctx_len, r = MID, 23, 210, 8
+    toks = ci.uniform_tokens(seed, "ctx_tokens", 0, ctx_len + r, shape.vocab).tolist()
+    out = []
+    for grid in (0, 192, 64, 100):
+        tgt = card.Target(shape, 256, grid_wgs=grid)
+        load_synthetic_weights(tgt, shape, seed, 0.2)
+        tgt.prefill(toks[:ctx_len], chunk=8)  # (chunks of eight: the r <= 8 kernel all the way)
+        res = tgt.verify(ctx_len, -1, toks[ctx_len:], want_logits=True)
+        k, v = tgt.kv_gather(shape.n_layers - 1, 0, ctx_len + r)
+        out.append((res["logits"].clone(), k, v, res["row_argmax"]))
+    for other in out[1:]:
+        assert torch.equal(other[0], out[0][0]) and torch.equal(other[1], out[0][1]) and torch.equal(other[2], out[0][2])
+        assert other[3] == out[0][3]
