@@ -238,3 +238,34 @@ def test_a_wide_level_in_calls_side_by_side_equals_the_calls_one_after_the_other
     for a, b in zip(out["row"], out["wide"]):
         assert torch.equal(a, b)
     assert (out["wide"][0] >= 0).all()
+
+
+@pytest.mark.parametrize("n", [8, 13, 29])
+def test_a_chain_forwarded_as_tree_rows_equals_the_verify_step_bit_for_bit(n):
+    """Tree rows whose mask is the plain causal chain (row i sees the context and rows 0..i, slots
+    = positions) are the rows of a verification step: card_draft_level must then give the logits
+    and keys of card_verify bit for bit - the tree mask, the separate positions and slots change
+    what a row sees, never how its sums are taken."""
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape, seed, ctx_len = MID, 31, 75
+    tgt = card.Target(shape, 192, max_r=32)
+    load_synthetic_weights(tgt, shape, seed, 0.2)
+    toks = ci.uniform_tokens(seed, "ctx_tokens", 0, ctx_len + n, shape.vocab).tolist()
+    tgt.prefill(toks[:ctx_len])
+    ref = tgt.verify(ctx_len, -1, toks[ctx_len:], want_logits=True)
+    k_ref, v_ref = tgt.kv_gather(shape.n_layers - 1, ctx_len, n)
+    mask_base = ctx_len // 16 * 16
+    words = (ctx_len + n - mask_base + 31) // 32
+    rows, prev = [], None
+    for i in range(n):
+        st, row = card.card_tree_mask_level(prev, [-1 if i == 0 else 0], ctx_len + i, ctx_len, mask_base, words)
+        rows.append(row[0])
+        prev = row
+    res = tgt.draft_level(ctx_len, toks[ctx_len:], [ctx_len + i for i in range(n)], ctx_len, rows, mask_base, 4, want_logits=True)
+    assert torch.equal(res["logits"], ref["logits"])
+    k, v = tgt.kv_gather(shape.n_layers - 1, ctx_len, n)
+    assert torch.equal(k, k_ref) and torch.equal(v, v_ref)
+    # the fused top-k's first entry is the arg-max the verify step reports
+    assert res["topk_tokens"][:, 0].tolist() == ref["row_argmax"]
