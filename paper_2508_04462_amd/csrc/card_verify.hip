@@ -8,7 +8,8 @@
 //   * four PRODUCER wavefronts per workgroup (one per SIMD) walk the workgroup's weight
 //     fragments of the whole step in consumption order, keep 8 loads of 1 KiB in flight each
 //     and push what arrives into a per-wavefront FIFO in LDS (28 KiB each).  The weights are
-//     stored in exactly that order, so each producer reads one contiguous run per matrix;
+//     stored in exactly that order, so each producer reads one contiguous run per matrix (four
+//     interleaved runs in the grouped down-projection of the kernels for r > 8: plan_phase_grouped);
 //   * four CONSUMER wavefronts pop fragments from their FIFO into the matrix pipe, run the
 //     epilogues, the attention phase and the grid barriers.
 //
