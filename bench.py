@@ -312,7 +312,8 @@ def concurrent_loop_entries(args, decode_tps, quick, grids=(192, 64)):
     d_shape = ci.ModelShape("tiny-draft", 1, 128, 2, 1, 64, 344, 1024) if quick else ci.SHAPES["llama1b"]
     ctx_len, n_tok = (128, 24) if quick else (1024, 64)
     depth, r_max = (3, 4) if quick else (12, 8)
-    runs = ((0.6, 0.0),) if quick else ((0.3, 0.0), (0.6, 0.0), (0.9, 0.0), (0.6, 0.6))
+    # (planted agreement, sibling catch, nodes per cache level; 50 is the paper's smaller cache size)
+    runs = ((0.6, 0.0, 8),) if quick else ((0.3, 0.0, 8), (0.6, 0.0, 8), (0.9, 0.0, 8), (0.6, 0.6, 8), (0.9, 0.0, 50))
     n_text = len(runs) * (n_tok + 60) + 24  # room to step over positions where the target's two best tokens nearly tie
     tgt = card.Target(t_shape, ctx_len + n_text + 64, grid_wgs=grids[0])
     load_synthetic_weights(tgt, t_shape, args.seed)
@@ -335,8 +336,7 @@ def concurrent_loop_entries(args, decode_tps, quick, grids=(192, 64)):
     tie = 0.0025  # (logits of about 7.5: differences of the summation order reach 0.001-0.002)
     out = []
     n_done = 0
-    # (planted agreement of the best path, of the second-best sibling where the best path is wrong)
-    for p, q in runs:
+    for p, q, K in runs:
         # each run continues the text behind the previous one, stepping over near ties
         span = n_tok + r_max + 2
         start = n_done
@@ -346,14 +346,14 @@ def concurrent_loop_entries(args, decode_tps, quick, grids=(192, 64)):
         # the stretch that is stepped over is decoded again
         for i in range(start, n_done):
             tgt.verify(ctx_len + i, own[i], [own[i]])
-        loop = card.ConcurrentLoop(tgt, dr, ctx_len + n_done, own[n_done], K=8, k=8, depth=depth, r_max=r_max,
+        loop = card.ConcurrentLoop(tgt, dr, ctx_len + n_done, own[n_done], K=K, k=8, depth=depth, r_max=r_max,
                                    plant=card.PlantedAgreement(own[n_done:], p, args.seed, t_shape.vocab, q=q))
         loop.d_ctx = ctx_len
         loop.committed = own[:n_done]
         loop.d_absorbed = 0
         e = {"kind": "concurrent_loop", "target": t_shape.name, "draft": d_shape.name, "ctx": ctx_len + n_done,
              "target_workgroups": grids[0], "draft_workgroups": grids[1], "planted_acceptance": p, "planted_sibling_catch": q,
-             "K": 8, "k": 8, "depth": depth, "r_max": r_max, "plain_decode_tokens_per_s_whole_gpu": decode_tps,
+             "K": K, "k": 8, "depth": depth, "r_max": r_max, "plain_decode_tokens_per_s_whole_gpu": decode_tps,
              "smallest_top2_gap_of_the_stretch": min(gaps[n_done: n_done + n_tok + r_max + 2])}
         try:
             res = loop.run(n_tok)

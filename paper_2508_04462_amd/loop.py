@@ -103,7 +103,8 @@ def _find(lv: _Level, token: int, parent: int) -> int:
 class ConcurrentLoop:
     """target, draft: Target objects on the same device with grid_wgs set so that both kernels fit.
     Both must have the prompt prefilled (context length ctx_len); `pending` is the target's token
-    for position ctx_len.  K (<= 32): nodes per cache level, k: top-k per node, depth: levels the
+    for position ctx_len.  K: nodes per cache level (the paper's 50 or 100 take several forward
+    calls per level, 32 rows each), k: top-k per node (K * k <= 2048), depth: levels the
     draft keeps below the token verified last, r_max: tokens the target verifies per step (the
     verified token and at most r_max - 1 levels of the best path; default depth + 1).
 
@@ -131,7 +132,7 @@ class ConcurrentLoop:
         temperature > 0: the target verifies by sampling (one draw per position from the seeded
         counter-based generator): the loop then emits the text of token-by-token sampling with that
         seed, as it emits the greedy text at temperature 0."""
-        assert 1 <= K <= 32 and 1 <= k <= 16 and depth >= 1
+        assert 1 <= K and K * k <= 2048 and 1 <= k <= 16 and depth >= 1  # (the selection pools at most 2048 tuples)
         self.tgt, self.dr = target, draft
         self.K, self.k, self.depth, self.plant = K, k, depth, plant
         self.r_max = min(depth + 1 if r_max is None else r_max, target.cfg.max_r)
@@ -278,14 +279,17 @@ class ConcurrentLoop:
                                               self.mask_base, self.words)
         if st != B.CARD_OK:
             raise B.CardError(st, "card_tree_mask_level")
-        res = dr.draft_level(self.d_ctx, [lv.tok[i] for i in alive], [self.pos0 + D] * len(alive), first, rows, self.mask_base,
-                             self.k)
         n = len(lv.tok)
         lv.tk = torch.full((n, self.k), -1, dtype=torch.int32, device=dev)
         lv.tp = torch.zeros((n, self.k), dtype=torch.float32, device=dev)
-        idx = torch.tensor(list(alive), dtype=torch.long, device=dev)
-        lv.tk.index_copy_(0, idx, res["topk_tokens"])
-        lv.tp.index_copy_(0, idx, res["topk_probs"])
+        toks = [lv.tok[i] for i in alive]
+        for c0 in range(0, len(alive), 32):  # a level wider than one call: peers never see each other
+            c1 = min(len(alive), c0 + 32)
+            res = dr.draft_level(self.d_ctx, toks[c0:c1], [self.pos0 + D] * (c1 - c0), first + c0, rows[c0:c1], self.mask_base,
+                                 self.k)
+            idx = torch.tensor(list(alive[c0:c1]), dtype=torch.long, device=dev)
+            lv.tk.index_copy_(0, idx, res["topk_tokens"])
+            lv.tp.index_copy_(0, idx, res["topk_probs"])
         for j, i in enumerate(alive):
             lv.slot[i], lv.row[i] = first + j, rows[j]
         self.next_slot += len(alive)

@@ -329,12 +329,13 @@ def test_concurrent_loop_with_a_draft_that_runs_ahead_of_its_target():
         pos += 1
     # the second: tree slots run out; the third: the best path is often wrong but a sibling carries the
     # target's token, so the tree is re-rooted on a node that is not the first of its level
+    # the fourth: the paper's K = 50 nodes per level (two forward calls per level)
     for K, dmax, p, q in ((8, ctx_len + n_new + 1100, 0.95, 0.0), (24, ctx_len + n_new + 360, 0.95, 0.0),
-                          (8, ctx_len + n_new + 1100, 0.5, 0.9)):
+                          (8, ctx_len + n_new + 1100, 0.5, 0.9), (50, ctx_len + n_new + 1100, 0.95, 0.0)):
         dr = card.Target(draft_shape, dmax, grid_wgs=64)
         load_synthetic_weights(dr, draft_shape, seed + 100)
         dr.prefill(ctx)
-        loop = card.ConcurrentLoop(tgt, dr, ctx_len, g0, K=K, k=4, depth=12, r_max=8,
+        loop = card.ConcurrentLoop(tgt, dr, ctx_len, g0, K=K, k=4, depth=12 if K < 50 else 8, r_max=8,
                                    plant=card.PlantedAgreement(own, p, seed, shape.vocab, q=q))
         out = loop.run(n_new)
         assert loop.emitted[: n_new + 1] == own[: n_new + 1]
