@@ -368,8 +368,10 @@ class ConcurrentLoop:
         def guard(fn, *args):
             try:
                 fn(*args)
-            except BaseException as e:  # noqa: BLE001  (reported by run())
-                self.error = e
+            except BaseException as e:  # noqa: BLE001  (reported by run(); the first one wins, and ends both threads)
+                if self.error is None:
+                    self.error = e
+                self.stop = True
             finally:
                 if fn == self._target_loop:
                     self.stop = True

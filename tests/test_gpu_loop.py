@@ -275,6 +275,43 @@ def test_concurrent_draft_and_target_on_one_gpu_is_lossless(p, seed, grids):
         assert out["mean_accepted_len"] == 1.0
 
 
+def test_a_failure_on_the_draft_side_ends_the_loop_with_that_error():
+    """Failure handling, forced from the host: the draft thread's planting callback raises after a
+    few levels.  run() ends both threads and raises that error (the target does not go on decoding
+    against a cache nobody fills); every kernel launched so far finishes normally, and the same
+    models run a fresh loop afterwards."""
+    import paper_2508_04462_amd as card
+    from paper_2508_04462_amd.synthetic import load_synthetic_weights
+
+    shape, n_new, seed = TINY, 200, 11
+    draft_shape = ci.ModelShape("tiny-draft", 1, 128, 2, 1, 64, 344, 1024, ctx=128, r=4)
+    tgt = card.Target(shape, shape.ctx + n_new + 16, grid_wgs=128)
+    load_synthetic_weights(tgt, shape, seed)
+    dr = card.Target(draft_shape, shape.ctx + n_new + 16 + 160, grid_wgs=64)
+    load_synthetic_weights(dr, draft_shape, seed + 100)
+    ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, shape.ctx, shape.vocab).tolist()
+    g0 = tgt.prefill(ctx)
+    dr.prefill(ctx)
+    calls = []
+
+    def failing_plant(index, level, tokens, parents, anchor, parent_tokens):
+        calls.append(index)
+        if len(calls) == 4:
+            raise ValueError("planted failure")
+        return list(tokens), list(parents)
+
+    loop = card.ConcurrentLoop(tgt, dr, shape.ctx, g0, K=8, k=4, depth=3, plant=failing_plant)
+    with pytest.raises(ValueError, match="planted failure"):
+        loop.run(n_new)
+    assert len(loop.emitted) - 1 < n_new  # the target stopped early
+    # the models are usable afterwards: a fresh loop from the state the first one left
+    loop2 = card.ConcurrentLoop(tgt, dr, shape.ctx, g0, K=8, k=4, depth=3)
+    tgt.prefill(ctx)
+    dr.prefill(ctx)
+    out = loop2.run(8)
+    assert out["tokens"] >= 8
+
+
 def test_concurrent_loop_at_temperature_one_emits_the_sampled_text():
     """Temperature 1 in the loop (the paper's T = 1 columns): with the target sampling from the seeded
     generator, the concurrent loop emits exactly what token-by-token sampling with the same seed
