@@ -29,8 +29,11 @@ Pins (tests/test_oracle_*.py): row-batched verify == token-by-token decode ==
 cache-free full recompute (a separate code path below); planted-prefix
 invariant; rotary, norm, softmax and GQA identities; blocks against torch's
 CPU library routines; sampling: draw frequencies against the softmax (chi-square),
-acceptance rate against p(c), chained steps against token-by-token sampling.  Absolute logit values have no printed example in the
-paper to compare with: "parity unpinned" beyond those pins.
+acceptance rate against p(c), chained steps against token-by-token sampling.
+The paper prints no numeric example of a forward pass; the logit values are pinned
+by the whole forward rebuilt from torch's CPU library routines and by the cache-free
+recompute, the decisions by brute force and the planted prefixes.  No function
+of this file is without a pin.
 """
 from __future__ import annotations
 
