@@ -144,6 +144,9 @@ def main():
     ap.add_argument("--r", type=int, default=None)
     ap.add_argument("--ctx", type=int, default=None)
     ap.add_argument("--window", type=int, default=0, help="greedy tokens to scan for a fully decisive run of r rows")
+    ap.add_argument("--chunk", type=int, default=128, help="rows per oracle forward call while the context is prefilled "
+                    "(the rows of a call are independent of how the context is cut; larger pieces only spread the "
+                    "per-call cost of widening the weights over more rows)")
     args = ap.parse_args()
     name, seed = args.shape, args.seed
     shape = ci.SHAPES[name]
@@ -155,7 +158,11 @@ def main():
     ctx = ci.uniform_tokens(seed, "ctx_tokens", 0, n_ctx, shape.vocab).tolist()
     n_new = max(r, args.window)
     kv = co.OracleKV.empty(shape, n_ctx + n_new + r + 8, dt)
-    g0 = co.prefill(shape, w, kv, ctx, dt, chunk=128)
+    # (co.prefill's own loop, written out so that a long context reports its progress)
+    for s0 in range(0, n_ctx, args.chunk):
+        last = co.forward_rows(shape, w, kv, ctx[s0: s0 + args.chunk], s0, dt)
+        print(f"prefilled {min(n_ctx, s0 + args.chunk)} of {n_ctx} {time.time() - t0:.0f}s", flush=True)
+    g0 = int(co.argmax_lowest(last[-1]))
     print(f"prefill done {time.time() - t0:.0f}s g0={g0}", flush=True)
     # decode in pieces of r tokens and stop at the first fully decisive run of r rows
     greedy, gaps = [g0], []
@@ -170,6 +177,7 @@ def main():
     rng = np.random.default_rng(1234)
     sample_idx = sorted(set(rng.integers(0, shape.vocab, size=48).tolist() + [int(t) for t in greedy[: r + 1]]))
     out = {"shape": name, "seed": seed, "ctx": n_ctx, "r": r, "oracle_dtype": str(np.dtype(dt)), "kv_store": kv.store,
+           "prefill_chunk": args.chunk,
            "greedy": [int(g) for g in greedy[: r + 1]], "greedy_gaps": [float(g) for g in gaps[:r]],
            "sample_idx": sample_idx}
 
