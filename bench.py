@@ -50,9 +50,61 @@ def parse():
                     help="for rocprofv3 --pmc runs: three cache levels of K = 100 nodes on the 1B-shaped draft, no timing")
     ap.add_argument("--loop-probe", action="store_true",
                     help="for rocprofv3 --kernel-trace runs: the concurrent draft/target loop alone (70B + 1B shapes)")
+    ap.add_argument("--timeline", type=int, default=None, metavar="LAYER",
+                    help="the kernel's own phase timeline (100 MHz time stamps per workgroup) of one decoder layer of one "
+                         "verify step of the workload: medians over the workgroups, no timing of the step")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a 1 GiB device copy (calibration) and 5 verify steps, no timing")
     return ap.parse_args()
+
+
+def phase_timeline(rig, ctx, r, cand, layer):
+    """One verify step with the library's timeline hook on decoder layer `layer`: per workgroup the
+    consumer wavefront 0 stamps the phase boundaries (card_profile_timeline).  Reported: per phase
+    the median over the workgroups of (this boundary - the previous one), in microseconds, and the
+    spread of each boundary (latest - earliest workgroup); the attention figures over the
+    workgroups that had an attention task."""
+    import numpy as np
+    import torch
+
+    import paper_2508_04462_amd as card
+
+    tgt = rig.tgt
+    for _ in range(5):
+        assert tgt.enqueue_verify(ctx, rig.g0, r, cand=cand) == card.CARD_OK
+    torch.cuda.synchronize()
+    ts = torch.zeros(256 * 32, dtype=torch.int64, device=tgt.device)
+    card.card_profile_timeline(ts, layer)
+    assert tgt.enqueue_verify(ctx, rig.g0, r, cand=cand) == card.CARD_OK
+    torch.cuda.synchronize()
+    card.card_profile_timeline(None, 0)
+    t = ts.cpu().numpy().reshape(256, 32).astype(np.float64) * 0.01  # microseconds
+    live = t[:, 0] > 0
+    t = t[live]
+    names = ["qkv", "barrier_after_qkv", "attention", "barrier_after_attention", "o_proj", "barrier_after_o_proj",
+             "gate_up", "barrier_after_gate_up", "down", "barrier_after_down"]
+    out = {"workgroups": int(live.sum()), "layer": layer, "unit": "us", "phases": {}, "boundary_spread": {}}
+    for i, n in enumerate(names):
+        out["phases"][n] = round(float(np.median(t[:, i + 1] - t[:, i])), 2)
+        out["boundary_spread"][n] = round(float(t[:, i + 1].max() - t[:, i + 1].min()), 2)
+    out["layer_total"] = round(float(np.median(t[:, 10] - t[:, 0])), 2)
+    for tag, s0 in (("qkv", 21), ("o_proj", 24), ("down", 27)):
+        d = {"first_activations_after": round(float(np.median(t[:, s0] - t[:, {21: 0, 24: 4, 27: 8}[s0]])), 2),
+             "k_loop": round(float(np.median(t[:, s0 + 1] - t[:, s0])), 2)}
+        if s0 != 27:
+            d["of_which_waiting_for_fragments"] = round(float(np.median(t[:, s0 + 2])), 2)
+        d["reduction_and_epilogue"] = round(float(np.median(t[:, {21: 1, 24: 5, 27: 9}[s0]] - t[:, s0 + 1])), 2)
+        out[tag + "_detail"] = d
+    att = t[t[:, 13] > 0]
+    if len(att):
+        out["attention_detail"] = {
+            "workgroups_with_a_task": int(len(att)),
+            "barrier_to_page_loop": round(float(np.median(att[:, 13] - att[:, 2])), 2),
+            "page_loop": round(float(np.median(att[:, 14] - att[:, 13])), 2),
+            "wavefronts_merged_after": round(float(np.median(att[:, 15] - att[:, 14])), 2),
+            "task_done_median": round(float(np.median(att[:, 3] - att[:, 2])), 2),
+            "last_merging_workgroup_done_after_barrier": round(float(att[:, 3].max() - np.median(att[:, 2])), 2)}
+    return {"timeline": out, "workload": f"{rig.shape.name} ctx {ctx} r {r}"}
 
 
 def step_bytes(shape, ctx: int) -> int:
@@ -578,6 +630,9 @@ def main():
         sys.exit(1)
     cand_dev = torch.tensor(cands, dtype=torch.int32, device=dev)
 
+    if args.timeline is not None:
+        print(json.dumps(phase_timeline(rig, ctx, r, cand_dev[r], args.timeline)))
+        return
     if args.pmc_probe:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)

@@ -256,7 +256,8 @@ int card_workspace_init(const card_model_cfg* cfg, void* workspace_dev, void* st
  * 14 left, 15 wavefronts merged, 29 partial stored, 30 arrival counted, 31 cuts merged;
  * 17-20 the producer of wavefront pair 0 starts streaming the QKV / O / gate-up / down matrix;
  * 21-23 / 24-26 / 27-28 QKV / O-projection / down phase: first activations arrived, k-loop left,
- * ticks the k-loop spent waiting for weight fragments (a duration, not a time stamp). */
+ * ticks the k-loop spent waiting for weight fragments (a duration, not a time stamp; the down
+ * phase has no such slot). */
 int card_profile_enable(int32_t max_launches);
 int card_profile_collect(float* ms_host, int32_t* n_host);
 int card_profile_disable(void);

@@ -541,7 +541,7 @@ struct LmState {
 
 struct EpiArgs {
     int32_t layer;
-    int32_t ts0;  // timeline slots of this phase: ts0 first activations in, ts0+1 k-loop left, ts0+2 ticks spent waiting for fragments; <= 0: none
+    int32_t ts0;  // timeline slots of this phase: ts0 first activations in, ts0+1 k-loop left, ts0+2 ticks spent waiting for fragments (not for the down-projection, whose third slot would be attention's); <= 0: none
     const float* ss_in;      // [32 rows][d/16] partial sums of squares of the input rows (norm phases)
     // RESID
     const float* xres_old;
@@ -761,7 +761,7 @@ __device__ __forceinline__ void gemm_phase(const MegaArgs& a, const PhasePlan& P
         if (b + 1 == n_batches) {
             if (gts) {
                 a.ts[size_t(blockIdx.x) * 32 + ea.ts0 + 1] = wall_clock64();
-                a.ts[size_t(blockIdx.x) * 32 + ea.ts0 + 2] = fc.waited - waited0;
+                if (ea.ts0 + 2 < 29) a.ts[size_t(blockIdx.x) * 32 + ea.ts0 + 2] = fc.waited - waited0;  // (29.. belong to attention)
             }
             after_k();
             hook_done = true;

@@ -56,3 +56,20 @@ def test_short_run_prints_one_json_line_with_the_contract_fields(monkeypatch, ca
     loops = [e for e in sw if e.get("kind") == "cache_loop"]
     assert loops and all("error" in e or (e["accepted_tokens_per_s"] > 0 and 1.0 <= e["mean_accepted_len"] <= e["r"])
                          for e in loops)
+
+
+@pytest.mark.gpu
+def test_timeline_probe_reports_the_ten_phases_of_a_layer(monkeypatch, capsys):
+    """bench.py --timeline: the kernel's own time stamps of one decoder layer, on the smallest shape."""
+    import runpy
+
+    monkeypatch.setattr(sys, "argv", ["bench.py", "--shape", "tiny", "--timeline", "1", "--sweep", "none", "--no-cpu-baseline"])
+    monkeypatch.chdir(ROOT)
+    runpy.run_path(os.path.join(ROOT, "bench.py"), run_name="__main__")
+    lines = [ln for ln in capsys.readouterr().out.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    t = json.loads(lines[0])["timeline"]
+    assert t["workgroups"] == 256 and len(t["phases"]) == 10
+    assert all(v >= 0 for v in t["phases"].values())  # the stamps of a workgroup are in order
+    assert 0 < t["layer_total"] < 1000 and abs(sum(t["phases"].values()) - t["layer_total"]) < 0.2 * t["layer_total"] + 1
+    assert t["attention_detail"]["workgroups_with_a_task"] >= 1
