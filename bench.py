@@ -94,6 +94,9 @@ def phase_timeline(rig, ctx, r, cand, layer):
         if s0 != 27:
             d["of_which_waiting_for_fragments"] = round(float(np.median(t[:, s0 + 2])), 2)
         d["reduction_and_epilogue"] = round(float(np.median(t[:, {21: 1, 24: 5, 27: 9}[s0]] - t[:, s0 + 1])), 2)
+        if s0 == 21:  # between the k-loop and the reduction the loads of the old context's pages are issued
+            d["of_which_page_preload_issue"] = round(float(np.median(t[:, 16] - t[:, 11])), 2)
+            d["stores_acknowledged_after"] = round(float(np.median(t[:, 12] - t[:, 1])), 2)
         out[tag + "_detail"] = d
     att = t[t[:, 13] > 0]
     if len(att):
