@@ -144,6 +144,8 @@ def main():
     ap.add_argument("--r", type=int, default=None)
     ap.add_argument("--ctx", type=int, default=None)
     ap.add_argument("--window", type=int, default=0, help="greedy tokens to scan for a fully decisive run of r rows")
+    ap.add_argument("--layers", type=int, default=0, help="reduced depth: the first N layers of the shape (for widths whose "
+                    "full depth does not fit the host: the 70B shape)")
     ap.add_argument("--chunk", type=int, default=128, help="rows per oracle forward call while the context is prefilled "
                     "(the rows of a call are independent of how the context is cut; larger pieces only spread the "
                     "per-call cost of widening the weights over more rows)")
@@ -152,6 +154,8 @@ def main():
     shape = ci.SHAPES[name]
     r = shape.r if args.r is None else args.r
     n_ctx = shape.ctx if args.ctx is None else args.ctx
+    if args.layers:
+        shape = shape.with_layers(args.layers)
     dt = np.float32 if shape.d_model >= 2048 else np.float64
     t0 = time.time()
     w = oracle_weights(shape, seed, dtype=dt)
@@ -177,7 +181,7 @@ def main():
     rng = np.random.default_rng(1234)
     sample_idx = sorted(set(rng.integers(0, shape.vocab, size=48).tolist() + [int(t) for t in greedy[: r + 1]]))
     out = {"shape": name, "seed": seed, "ctx": n_ctx, "r": r, "oracle_dtype": str(np.dtype(dt)), "kv_store": kv.store,
-           "prefill_chunk": args.chunk,
+           "prefill_chunk": args.chunk, "layers": shape.n_layers,
            "greedy": [int(g) for g in greedy[: r + 1]], "greedy_gaps": [float(g) for g in gaps[:r]],
            "sample_idx": sample_idx}
 
@@ -211,7 +215,7 @@ def main():
         cases.append(case_record(res, cand, j, sample_idx))
         print(f"case j={j} accepted {res.accepted_len} {time.time() - t0:.0f}s", flush=True)
     out["cases"] = cases
-    suffix = "" if n_ctx == shape.ctx else f"_ctx{n_ctx}"
+    suffix = ("" if n_ctx == ci.SHAPES[name].ctx else f"_ctx{n_ctx}") + (f"_L{args.layers}" if args.layers else "")
     path = os.path.join(GOLDEN, f"{name}_seed{seed}{suffix}.json")
     with open(path, "w") as f:
         json.dump(out, f)
